@@ -1,0 +1,147 @@
+/*
+ * moe355 -- forward pass of one Mixture-of-Experts layer on AMD MI355X (gfx950),
+ * with FP8 (e4m3) block-scaled expert GEMMs and a Router Replay mode.
+ *
+ * The operations follow the paper's statement of the problem:
+ *   - Router Replay (section 2.4.4): the expert choices made by the router at
+ *     rollout time are recorded and reused verbatim when the layer is evaluated
+ *     again, instead of being recomputed.
+ *   - FP8 rollout (section 3.1.2): weights arrive block-wise quantised to FP8
+ *     and activations are quantised to FP8 on the fly, for Linear and MoE layers.
+ * The paper gives no formulas for the layer; each entry point below states the
+ * definition it implements.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer owned by the caller.  The library
+ *     neither frees nor keeps it after the call returns.
+ *   - All work is enqueued on the HIP stream given to moe_create(); calls return
+ *     without synchronising.  A context must not be used from two threads at once.
+ *   - Notation: T tokens, d hidden size, E experts, k experts per token, F expert
+ *     FFN width, N = T*k assignments.  d and F must be multiples of 128.
+ *   - bf16 values are passed as uint16_t bit patterns, e4m3 codes as uint8_t
+ *     (OCP "FN" variant: bias 7, max 448, no infinities, 0x7F/0xFF = NaN).
+ *   - Return value: 0 on success, a negative MOE_E* code otherwise.  On an error
+ *     detected by argument validation nothing has been enqueued.
+ */
+#ifndef MOE355_H
+#define MOE355_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MOE_OK        0
+#define MOE_EINVAL   -1   /* null pointer, bad shape, d or F not a multiple of 128, k > E, block != 128 */
+#define MOE_EHIP     -2   /* a HIP runtime call or kernel launch failed */
+#define MOE_EBADIDS  -3   /* moe_check_ids found an expert id outside [0,E) */
+#define MOE_ENOMEM   -4   /* workspace allocation failed */
+
+typedef struct moe_ctx moe_ctx;
+
+typedef struct {
+    int32_t T;  /* tokens per call (upper bound is not needed: exact) */
+    int32_t d;  /* hidden size, multiple of 128 */
+    int32_t E;  /* experts, 1..256 */
+    int32_t k;  /* experts per token, 1..min(E,16) */
+    int32_t F;  /* expert FFN width, multiple of 128 */
+} moe_dims;
+
+/* Create a context for one layer shape.  Allocates the internal device workspace
+ * (chunk histograms, the tile work list, and the quantised hidden activations
+ * hq [N,F] u8 + hs [N,F/128] f32).  hip_stream is a hipStream_t (NULL = default
+ * stream).  The device current at creation must be current at every later call. */
+int moe_create(moe_ctx** out, const moe_dims* dims, void* hip_stream);
+int moe_destroy(moe_ctx* ctx);
+const char* moe_strerror(int code);
+
+/* Routed mode.  logit[t,e] = sum_c x[t,c]*W_router[e,c] (fp32 accumulation);
+ * score = logit + sel_bias[e] (sel_bias may be NULL = 0; it affects selection
+ * only).  topk_idx[t,0..k-1] = the k experts of largest score in descending
+ * score order, equal scores resolved towards the lower expert index.
+ * topk_w[t,j] = softmax over the k selected unbiased logits.  Then the stable
+ * permutation of moe_route_replay is built from topk_idx.
+ *   x_bf16 [T,d] row-major; W_router [E,d] fp32 row-major; sel_bias [E] or NULL.
+ *   Outputs: topk_idx [T,k] i32, topk_w [T,k] f32, offsets [E+1] i32,
+ *   perm [N] i32, inv_perm [N] i32.
+ * k must equal the context's k. */
+int moe_route(moe_ctx* ctx, const uint16_t* x_bf16, const float* W_router, const float* sel_bias,
+              int32_t k, int32_t* topk_idx, float* topk_w,
+              int32_t* offsets, int32_t* perm, int32_t* inv_perm);
+
+/* Router Replay mode (section 2.4.4).  logged_idx/logged_w are copied verbatim to
+ * topk_idx/topk_w: no router GEMM, no softmax, no renormalisation.  x_bf16 is
+ * accepted for symmetry with moe_route and is not read (may be NULL).
+ * The permutation is the stable counting sort of flat assignments i = t*k+j by
+ * expert id: offsets[e] = number of assignments with id < e, offsets[E] = N;
+ * inv_perm[i] = offsets[id_i] + #{i' < i : id_i' = id_i}; perm[inv_perm[i]] = i.
+ * Ids outside [0,E) never fault; their assignments are skipped and a device flag
+ * is raised that moe_check_ids reports. */
+int moe_route_replay(moe_ctx* ctx, const uint16_t* x_bf16, const int32_t* logged_idx,
+                     const float* logged_w, int32_t* topk_idx, float* topk_w,
+                     int32_t* offsets, int32_t* perm, int32_t* inv_perm);
+
+/* Synchronises the stream and returns MOE_EBADIDS if any routing call on this
+ * context since the last check met an expert id outside [0,E), else MOE_OK. */
+int moe_check_ids(moe_ctx* ctx);
+
+/* Per-row FP8 quantisation with optional fan-out to expert order.
+ * For each input row r and each group g of `block` (=128) consecutive columns:
+ *   amax = max|x[r,g]|; s = amax/448 in fp32 (1.0 if amax = 0);
+ *   code = e4m3(x/s), fp32 division, round to nearest even, saturating.
+ * dst_rows == NULL: output row r receives input row r (fanout must be 1).
+ * Otherwise output rows dst_rows[r*fanout + j], j < fanout, all receive the
+ * quantised input row r (pass inv_perm and fanout = k to build the expert-ordered
+ * activation matrix in one pass over x).
+ *   x_bf16 [rows_in, cols]; q [rows_in*fanout, cols] u8;
+ *   scales [rows_in*fanout, cols/128] f32.  cols must be a multiple of 128.
+ * Does not use the context's T/d: any rows_in >= 0 and cols are accepted. */
+int moe_quantize_fp8(moe_ctx* ctx, const uint16_t* x_bf16, int64_t rows_in, int32_t cols,
+                     int32_t block, const int32_t* dst_rows, int32_t fanout,
+                     uint8_t* q, float* scales);
+
+/* Grouped SwiGLU expert FFN on expert-sorted rows.  For expert e and rows
+ * p in [offsets[e], offsets[e+1]):
+ *   g[p,f] = sum_kb xs[p,kb]*s1[e,f/128,kb] * sum_{c in block kb} xq[p,c]*W1[e,f,c]
+ *   u[p,f] = the same with W3, s3
+ *   h = g/(1+exp(-g)) * u (fp32), quantised per row per 128 columns exactly like
+ *       moe_quantize_fp8 -> hq, hs (kept in the context workspace)
+ *   y_perm[p,c] = sum_fb hs[p,fb]*s2[e,c/128,fb] * sum_{f in block fb} hq[p,f]*W2[e,c,f]
+ * FP8 products are accumulated in fp32 on the matrix cores, one 128-wide block at
+ * a time, and each block's partial sum is scaled in fp32.
+ *   xq_perm [N,d] u8; xs_perm [N,d/128] f32; offsets [E+1] i32 (device);
+ *   W1,W3 [E,F,d] u8; W2 [E,d,F] u8; s1,s3 [E,F/128,d/128] f32; s2 [E,d/128,F/128] f32;
+ *   y_perm [N,d] f32. */
+int moe_expert_ffn_fp8(moe_ctx* ctx, const uint8_t* xq_perm, const float* xs_perm,
+                       const int32_t* offsets, const uint8_t* W1, const uint8_t* W3,
+                       const uint8_t* W2, const float* s1, const float* s3, const float* s2,
+                       float* y_perm);
+
+/* Weighted combine back to token order:
+ *   y[t,c] = bf16( sum_{j<k} topk_w[t,j] * y_perm[inv_perm[t*k+j], c] ),
+ * fp32 fused multiply-adds in slot order, one rounding to bf16 at the end.
+ *   y_perm [N,d] f32; inv_perm [N] i32; topk_w [T,k] f32; y_bf16 [T,d]. */
+int moe_combine(moe_ctx* ctx, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
+                uint16_t* y_bf16);
+
+/* Device pointers to the hidden activations written by the last
+ * moe_expert_ffn_fp8 call (hq [N,F] u8, hs [N,F/128] f32); valid until the
+ * context is destroyed.  For stage-isolated checks. */
+int moe_debug_hidden(moe_ctx* ctx, const uint8_t** hq, const float** hs);
+
+/* Kernel timing for benchmarks.  While enabled, moe_expert_ffn_fp8 brackets its two
+ * GEMM kernels with HIP events on the context's stream (at most 512 calls are kept
+ * between reads).  moe_profile_read synchronises the stream, writes the MEAN
+ * duration in milliseconds of {gate/up GEMM, down GEMM} over the recorded calls to
+ * ms[0..1] and the number of calls to *calls, and clears the record. */
+int moe_profile_enable(moe_ctx* ctx, int32_t on);
+int moe_profile_read(moe_ctx* ctx, float* ms, int32_t* calls);
+
+/* Library version string. */
+const char* moe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MOE355_H */

@@ -1,0 +1,155 @@
+"""ctypes binding of libmoe355.so: argument marshalling only.
+
+Every function here has the name of the C entry point it calls (see
+include/moe355.h); tensors are torch CUDA tensors used purely as device
+memory.  There is no CPU fallback: if the shared library is missing or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libmoe355.so")
+_lib: Optional[ctypes.CDLL] = None
+
+EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_check_ids",
+           "moe_quantize_fp8", "moe_expert_ffn_fp8", "moe_combine", "moe_debug_hidden", "moe_profile_enable",
+           "moe_profile_read", "moe_version")
+
+
+class MoEError(RuntimeError):
+    pass
+
+
+class _Dims(ctypes.Structure):
+    _fields_ = [("T", ctypes.c_int32), ("d", ctypes.c_int32), ("E", ctypes.c_int32),
+                ("k", ctypes.c_int32), ("F", ctypes.c_int32)]
+
+
+def load_library(path: Optional[str] = None) -> ctypes.CDLL:
+    """Load libmoe355.so (built by paper_2512_07710_amd.build); raises if it is not there."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise MoEError(f"{p} not found: build it with `python -m paper_2512_07710_amd.build` "
+                       "(there is no fallback implementation)")
+    lib = ctypes.CDLL(p)
+    vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+    lib.moe_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(_Dims), vp]
+    lib.moe_destroy.argtypes = [vp]
+    lib.moe_strerror.argtypes = [ctypes.c_int]
+    lib.moe_strerror.restype = ctypes.c_char_p
+    lib.moe_version.restype = ctypes.c_char_p
+    lib.moe_route.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
+    lib.moe_route_replay.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.moe_check_ids.argtypes = [vp]
+    lib.moe_quantize_fp8.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp]
+    lib.moe_expert_ffn_fp8.argtypes = [vp] * 11
+    lib.moe_combine.argtypes = [vp] * 5
+    lib.moe_debug_hidden.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    lib.moe_profile_enable.argtypes = [vp, i32]
+    lib.moe_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
+    for name in EXPORTS:
+        if name not in ("moe_strerror", "moe_version"):
+            getattr(lib, name).restype = ctypes.c_int
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != 0:
+        raise MoEError(f"{what} failed: {load_library().moe_strerror(rc).decode()} ({rc})")
+
+
+def _ptr(t: Optional[torch.Tensor], dtype=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise MoEError("expected a contiguous CUDA tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise MoEError(f"expected dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def moe_create(T: int, d: int, E: int, k: int, F: int, stream: Optional[torch.cuda.Stream] = None) -> int:
+    """Returns an opaque context handle bound to `stream` (default: torch's current stream)."""
+    lib = load_library()
+    s = stream if stream is not None else torch.cuda.current_stream()
+    dims = _Dims(T, d, E, k, F)
+    h = ctypes.c_void_p()
+    _check(lib.moe_create(ctypes.byref(h), ctypes.byref(dims), ctypes.c_void_p(s.cuda_stream)), "moe_create")
+    return h.value
+
+
+def moe_destroy(ctx: int) -> None:
+    _check(load_library().moe_destroy(ctx), "moe_destroy")
+
+
+def moe_version() -> str:
+    return load_library().moe_version().decode()
+
+
+def moe_route(ctx, x, W_router, sel_bias, k, topk_idx, topk_w, offsets, perm, inv_perm) -> None:
+    _check(load_library().moe_route(ctx, _ptr(x, torch.bfloat16), _ptr(W_router, torch.float32),
+                                    _ptr(sel_bias, torch.float32), k, _ptr(topk_idx, torch.int32),
+                                    _ptr(topk_w, torch.float32), _ptr(offsets, torch.int32),
+                                    _ptr(perm, torch.int32), _ptr(inv_perm, torch.int32)), "moe_route")
+
+
+def moe_route_replay(ctx, x, logged_idx, logged_w, topk_idx, topk_w, offsets, perm, inv_perm) -> None:
+    _check(load_library().moe_route_replay(ctx, _ptr(x), _ptr(logged_idx, torch.int32),
+                                           _ptr(logged_w, torch.float32), _ptr(topk_idx, torch.int32),
+                                           _ptr(topk_w, torch.float32), _ptr(offsets, torch.int32),
+                                           _ptr(perm, torch.int32), _ptr(inv_perm, torch.int32)),
+           "moe_route_replay")
+
+
+def moe_check_ids(ctx) -> int:
+    """Returns the raw status (0 or MOE_EBADIDS) after synchronising the context's stream."""
+    return load_library().moe_check_ids(ctx)
+
+
+def moe_quantize_fp8(ctx, x, rows_in, cols, block, dst_rows, fanout, q, scales) -> None:
+    _check(load_library().moe_quantize_fp8(ctx, _ptr(x, torch.bfloat16), rows_in, cols, block,
+                                           _ptr(dst_rows, torch.int32), fanout, _ptr(q, torch.uint8),
+                                           _ptr(scales, torch.float32)), "moe_quantize_fp8")
+
+
+def moe_expert_ffn_fp8(ctx, xq_perm, xs_perm, offsets, W1, W3, W2, s1, s3, s2, y_perm) -> None:
+    u8, f32 = torch.uint8, torch.float32
+    _check(load_library().moe_expert_ffn_fp8(ctx, _ptr(xq_perm, u8), _ptr(xs_perm, f32),
+                                             _ptr(offsets, torch.int32), _ptr(W1, u8), _ptr(W3, u8),
+                                             _ptr(W2, u8), _ptr(s1, f32), _ptr(s3, f32), _ptr(s2, f32),
+                                             _ptr(y_perm, f32)), "moe_expert_ffn_fp8")
+
+
+def moe_combine(ctx, y_perm, inv_perm, topk_w, y) -> None:
+    _check(load_library().moe_combine(ctx, _ptr(y_perm, torch.float32), _ptr(inv_perm, torch.int32),
+                                      _ptr(topk_w, torch.float32), _ptr(y, torch.bfloat16)), "moe_combine")
+
+
+def moe_debug_hidden(ctx):
+    """Raw device addresses (hq, hs) of the hidden activations kept in the context."""
+    a, b = ctypes.c_void_p(), ctypes.c_void_p()
+    _check(load_library().moe_debug_hidden(ctx, ctypes.byref(a), ctypes.byref(b)), "moe_debug_hidden")
+    return a.value, b.value
+
+
+def moe_profile_enable(ctx, on: bool) -> None:
+    _check(load_library().moe_profile_enable(ctx, 1 if on else 0), "moe_profile_enable")
+
+
+def moe_profile_read(ctx):
+    """(mean ms of the gate/up GEMM, mean ms of the down GEMM, recorded calls); synchronises."""
+    ms = (ctypes.c_float * 2)()
+    n = ctypes.c_int32()
+    _check(load_library().moe_profile_read(ctx, ms, ctypes.byref(n)), "moe_profile_read")
+    return float(ms[0]), float(ms[1]), int(n.value)

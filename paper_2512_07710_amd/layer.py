@@ -1,0 +1,93 @@
+"""Buffer management around the C-ABI calls: one MoE layer shape on one GPU.
+
+`MoELayer` owns the output and intermediate device buffers (torch tensors used
+as plain device memory) and issues the five library calls in order.  All
+arithmetic happens inside libmoe355.
+"""
+from __future__ import annotations
+
+import ctypes
+from typing import Dict, Optional
+
+import torch
+
+from . import binding as B
+
+
+class MoELayer:
+    def __init__(self, T: int, d: int, E: int, k: int, F: int, device="cuda:0",
+                 stream: Optional[torch.cuda.Stream] = None):
+        self.T, self.d, self.E, self.k, self.F = T, d, E, k, F
+        self.N = T * k
+        self.device = torch.device(device)
+        with torch.cuda.device(self.device):
+            self.stream = stream if stream is not None else torch.cuda.current_stream()
+            self.ctx = B.moe_create(T, d, E, k, F, self.stream)
+        dev, N = self.device, max(self.N, 1)
+        self.topk_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
+        self.topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
+        self.offsets = torch.empty((E + 1,), dtype=torch.int32, device=dev)
+        self.perm = torch.empty((N,), dtype=torch.int32, device=dev)
+        self.inv_perm = torch.empty((N,), dtype=torch.int32, device=dev)
+        self.xq = torch.empty((N, d), dtype=torch.uint8, device=dev)
+        self.xs = torch.empty((N, d // 128), dtype=torch.float32, device=dev)
+        self.y_perm = torch.empty((N, d), dtype=torch.float32, device=dev)
+        self.y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+
+    def close(self):
+        if getattr(self, "ctx", None):
+            B.moe_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- the five stages ------------------------------------------------------------
+    def route(self, x, W_r, sel_bias=None):
+        B.moe_route(self.ctx, x, W_r, sel_bias, self.k, self.topk_idx, self.topk_w, self.offsets, self.perm,
+                    self.inv_perm)
+
+    def route_replay(self, x, logged_idx, logged_w):
+        B.moe_route_replay(self.ctx, x, logged_idx, logged_w, self.topk_idx, self.topk_w, self.offsets,
+                           self.perm, self.inv_perm)
+
+    def quantize(self, x):
+        B.moe_quantize_fp8(self.ctx, x, self.T, self.d, 128, self.inv_perm, self.k, self.xq, self.xs)
+
+    def expert_ffn(self, w: Dict[str, torch.Tensor]):
+        B.moe_expert_ffn_fp8(self.ctx, self.xq, self.xs, self.offsets, w["W1q"], w["W3q"], w["W2q"], w["s1"],
+                             w["s3"], w["s2"], self.y_perm)
+
+    def combine(self):
+        B.moe_combine(self.ctx, self.y_perm, self.inv_perm, self.topk_w, self.y)
+
+    # ---- whole layer ----------------------------------------------------------------
+    def forward_routed(self, x, W_r, sel_bias, w):
+        self.route(x, W_r, sel_bias)
+        self.quantize(x)
+        self.expert_ffn(w)
+        self.combine()
+        return self.y
+
+    def forward_replay(self, x, logged_idx, logged_w, w):
+        self.route_replay(x, logged_idx, logged_w)
+        self.quantize(x)
+        self.expert_ffn(w)
+        self.combine()
+        return self.y
+
+    def hidden(self):
+        """Copies of (hq [N,F] u8, hs [N,F/128] f32) written by the last expert_ffn call."""
+        a, b = B.moe_debug_hidden(self.ctx)
+        N, F = max(self.N, 1), self.F
+        hq = torch.empty((N, F), dtype=torch.uint8, device=self.device)
+        hs = torch.empty((N, F // 128), dtype=torch.float32, device=self.device)
+        rt = ctypes.CDLL("libamdhip64.so")
+        rt.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+        torch.cuda.synchronize(self.device)
+        assert rt.hipMemcpy(hq.data_ptr(), a, hq.numel(), 3) == 0
+        assert rt.hipMemcpy(hs.data_ptr(), b, hs.numel() * 4, 3) == 0
+        return hq, hs
