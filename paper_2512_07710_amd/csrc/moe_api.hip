@@ -51,13 +51,13 @@ int moe_create(moe_ctx** out, const moe_dims* dims, void* hip_stream) {
     const size_t nrow = (size_t)(N > 0 ? N : 1);
     bool ok = true;
     ok = ok && hipMalloc((void**)&c->chunk_counts, sizeof(int32_t) * (size_t)c->n_chunks * dims->E) == hipSuccess;
-    ok = ok && hipMalloc((void**)&c->tiles, sizeof(Tile) * (size_t)c->max_tiles) == hipSuccess;
-    ok = ok && hipMalloc((void**)&c->n_tiles, sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->tiles, ffn_work_bytes(c->max_tiles, dims->F, dims->d)) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->n_tiles, 4 * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->flags, 4 * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hq, nrow * (size_t)dims->F) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hs, nrow * (size_t)(dims->F / QBLOCK) * sizeof(float)) == hipSuccess;
     ok = ok && hipMemsetAsync(c->flags, 0, 4 * sizeof(int32_t), c->stream) == hipSuccess;
-    ok = ok && hipMemsetAsync(c->n_tiles, 0, sizeof(int32_t), c->stream) == hipSuccess;
+    ok = ok && hipMemsetAsync(c->n_tiles, 0, 4 * sizeof(int32_t), c->stream) == hipSuccess;
     if (!ok) {
         (void)hipGetLastError();
         moe_destroy(c);

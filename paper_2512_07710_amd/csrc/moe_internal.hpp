@@ -8,13 +8,11 @@ namespace moe355 {
 
 constexpr int QBLOCK = 128;        // quantisation group (activations 1x128, weights 128x128)
 constexpr int PERM_CHUNK = 2048;   // assignments handled by one block of the permutation kernels
-constexpr int TOK_TILE = 128;      // expert-sorted rows per GEMM tile
-constexpr int FEAT_TILE = 128;     // output features per GEMM tile
+constexpr int TOK_TILE = 256;      // expert-sorted rows per GEMM tile
 constexpr int MAX_E = 256;
 constexpr int MAX_K = 16;
 constexpr int PROF_MAX_CALLS = 512;
 
-struct Tile { int32_t expert; int32_t row0; };
 
 }  // namespace moe355
 
@@ -25,8 +23,8 @@ struct moe_ctx {
     int n_chunks;            // ceil(N / PERM_CHUNK)
     int max_tiles;           // upper bound on GEMM row tiles: N/TOK_TILE + E
     int32_t* chunk_counts;   // [n_chunks][E] per-chunk histograms, then their exclusive scans
-    moe355::Tile* tiles;     // [max_tiles]
-    int32_t* n_tiles;        // [1]
+    void* tiles;             // GEMM work lists (gate/up list, then down list)
+    int32_t* n_tiles;        // [2] their lengths
     int32_t* flags;          // [4] flags[0] != 0: an expert id outside [0,E) was met
     uint8_t* hq;             // [N][F]
     float* hs;               // [N][F/128]
@@ -47,6 +45,7 @@ hipError_t launch_quantize(hipStream_t s, const uint16_t* x, int64_t rows_in, in
 hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, const int32_t* offsets,
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2,
                              const float* s1, const float* s3, const float* s2, float* y_perm);
+size_t ffn_work_bytes(int max_tiles, int F, int d);
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm,
                           const float* topk_w, uint16_t* y);
 
