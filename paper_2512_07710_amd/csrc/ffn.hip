@@ -220,6 +220,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[s][ts][r] = 0.f;
 
+    float wsa_next = sa_e[0], wsb_next = sb_e[0];
     issue_stage(0, 0);
     for (int kb = 0; kb < nkb; ++kb) {
         const int buf = kb & 1;
@@ -230,8 +231,11 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
         if (wave_active) {
             const uint8_t* sW = s_stage + buf * STAGE_BYTES;
             const uint8_t* sX = sW + W_ROWS * KB;
-            const float wsa = sa_e[kb];
-            const float wsb = sb_e[kb];
+            const float wsa = wsa_next, wsb = wsb_next;        // loaded one iteration ahead
+            if (kb + 1 < nkb) {
+                wsa_next = sa_e[kb + 1];
+                wsb_next = sb_e[kb + 1];
+            }
             v8i b[2][2];
             float sc_a[2], sc_b[2];
 #pragma unroll
@@ -243,22 +247,39 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                 sc_a[ts] = xsc * wsa;
                 sc_b[ts] = xsc * wsb;
             }
+            // Software pipeline over the 8 (weight sub-tile s, token sub-tile ts) pairs: the two
+            // MFMAs of pair i are issued before the 16 scale-FMAs of pair i-1, so the matrix
+            // pipe works on pair i while the vector ALU folds pair i-1 into the accumulators.
+            const int wrow0 = wf * 128 + l32;
+            v8i a0 = load_operand(sW, wrow0, 0, half);
+            v8i a1 = load_operand(sW, wrow0, 1, half);
+            v16f zero;
 #pragma unroll
-            for (int s = 0; s < 4; ++s) {
-                const int wrow = wf * 128 + s * 32 + l32;
-                const v8i a0 = load_operand(sW, wrow, 0, half);
-                const v8i a1 = load_operand(sW, wrow, 1, half);
+            for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+            v16f prev = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, b[0][0], zero, 0, 0, 0, 0, 0, 0);
+            prev = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, b[0][1], prev, 0, 0, 0, 0, 0, 0);
 #pragma unroll
-                for (int ts = 0; ts < 2; ++ts) {
-                    v16f part;
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) part[r] = 0.f;
-                    part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, b[ts][0], part, 0, 0, 0, 0, 0, 0);
-                    part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, b[ts][1], part, 0, 0, 0, 0, 0, 0);
-                    const float sc = (GATED && s >= 2) ? sc_b[ts] : sc_a[ts];
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[s][ts][r] = fmaf(sc, part[r], acc[s][ts][r]);
+            for (int i = 1; i < 8; ++i) {
+                const int s = i >> 1, ts = i & 1;
+                if (ts == 0) {
+                    a0 = load_operand(sW, wrow0 + s * 32, 0, half);
+                    a1 = load_operand(sW, wrow0 + s * 32, 1, half);
                 }
+                __builtin_amdgcn_sched_barrier(0);
+                v16f cur = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, b[ts][0], zero, 0, 0, 0, 0, 0, 0);
+                cur = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, b[ts][1], cur, 0, 0, 0, 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                const int ps = (i - 1) >> 1, pts = (i - 1) & 1;
+                const float sc = (GATED && ps >= 2) ? sc_b[pts] : sc_a[pts];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[ps][pts][r] = fmaf(sc, prev[r], acc[ps][pts][r]);
+                __builtin_amdgcn_sched_barrier(0);
+                prev = cur;
+            }
+            {
+                const float sc = GATED ? sc_b[1] : sc_a[1];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[3][1][r] = fmaf(sc, prev[r], acc[3][1][r]);
             }
         }
     }
