@@ -54,6 +54,7 @@ int moe_create(moe_ctx** out, const moe_dims* dims, void* hip_stream) {
     ok = ok && hipMalloc((void**)&c->tiles, ffn_work_bytes(c->max_tiles, dims->F, dims->d)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->n_tiles, 4 * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->flags, 4 * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->router_planes, route_workspace_bytes(dims->E, dims->d)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hq, nrow * (size_t)dims->F) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hs, nrow * (size_t)(dims->F / QBLOCK) * sizeof(float)) == hipSuccess;
     ok = ok && hipMemsetAsync(c->flags, 0, 4 * sizeof(int32_t), c->stream) == hipSuccess;
@@ -74,6 +75,7 @@ int moe_destroy(moe_ctx* c) {
     if (c->tiles) (void)hipFree(c->tiles);
     if (c->n_tiles) (void)hipFree(c->n_tiles);
     if (c->flags) (void)hipFree(c->flags);
+    if (c->router_planes) (void)hipFree(c->router_planes);
     if (c->hq) (void)hipFree(c->hq);
     if (c->hs) (void)hipFree(c->hs);
     if (c->prof_events) {

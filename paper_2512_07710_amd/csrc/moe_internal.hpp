@@ -26,6 +26,7 @@ struct moe_ctx {
     void* tiles;             // GEMM work lists (gate/up list, then down list)
     int32_t* n_tiles;        // [2] their lengths
     int32_t* flags;          // [4] flags[0] != 0: an expert id outside [0,E) was met
+    uint16_t* router_planes; // router weights split into three bf16 planes, matrix-core order
     uint8_t* hq;             // [N][F]
     float* hs;               // [N][F/128]
     // optional kernel timing: three events per recorded expert-FFN call
@@ -46,6 +47,7 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, con
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2,
                              const float* s1, const float* s3, const float* s2, float* y_perm);
 size_t ffn_work_bytes(int max_tiles, int F, int d);
+size_t route_workspace_bytes(int E, int d);
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm,
                           const float* topk_w, uint16_t* y);
 

@@ -1,172 +1,253 @@
-// Router GEMM fused with top-k selection and gate weights (routed mode).
+// Router GEMM on the bf16 matrix cores, fused with top-k selection and gate weights.
 //
-// One block scores TT tokens against all E experts: logits are accumulated in
-// fp32 from bf16 activations and fp32 router weights staged through LDS, then
-// each wave picks the top k of a token with shuffle reductions (larger score
-// wins, equal scores go to the lower expert index) and turns the k selected
-// unbiased logits into softmax gate weights.
+// The fp32 router matrix is first split into three bf16 planes (hi + mid + lo reproduces
+// every fp32 weight exactly), stored in the order the matrix cores consume them.  Since
+// the activations are bf16 already, every product x*w_plane is exact in fp32 and the
+// accumulated logit is as accurate as an fp32 FMA chain, at matrix-core speed.
+//
+// One block scores 128 tokens against all experts.  Wave w owns a quarter of the
+// (padded) experts: its weight operands come straight from global memory, fully
+// coalesced, while the 128-token activation tile is staged through LDS and shared by
+// the four waves.  The product is taken as (experts x tokens), so a lane owns one
+// token column; each lane pair then extracts the k best of the wave's experts for its
+// token with register scans and one cross-half shuffle per round (larger score wins,
+// equal scores go to the lower expert index), and a final pass merges the four waves'
+// candidates, applies the softmax over the k selected unbiased logits and writes out.
 #include "moe_internal.hpp"
 
 namespace moe355 {
 namespace {
 
-constexpr int TT = 16;    // tokens per block
-constexpr int KC = 32;    // hidden columns staged per step
-constexpr int WPAD = 4;   // row padding (floats) of the staged router tile
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
-__device__ inline float bf16_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+constexpr int RT = 128;          // tokens per block
+constexpr int RKC = 64;          // hidden columns per staged activation chunk (128 bytes per row)
+constexpr int NO_CAND = 0x7FFFFFFF;
 
-// EP: expert count padded to a power of two in [32,256]; 256/EP thread groups split each K step.
-template <int EP>
-__global__ __launch_bounds__(256) void route_kernel(const uint16_t* __restrict__ x,
-                                                    const float* __restrict__ W,
-                                                    const float* __restrict__ bias, int T, int d, int E,
-                                                    int k, int32_t* __restrict__ topk_idx,
-                                                    float* __restrict__ topk_w) {
-    constexpr int GRP = 256 / EP;      // thread groups sharing one expert column
-    constexpr int CPG = KC / GRP;      // hidden columns per group per step (multiple of 4)
-    static_assert(CPG % 4 == 0, "column split must keep float4 granularity");
-    constexpr int VPT = (EP + 63) / 64;
+__device__ inline uint32_t f32_to_bf16_rne_bits(float v) {
+    const uint32_t b = __float_as_uint(v);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+__device__ inline float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 
-    __shared__ float xs[TT][KC];
-    // the staged router tile; the thread groups' partial sums reuse its storage afterwards
-    constexpr int WS_FLOATS = EP * (KC + WPAD) > GRP * TT * EP ? EP * (KC + WPAD) : GRP * TT * EP;
-    __shared__ float ws_raw[WS_FLOATS];
-    float (*ws)[KC + WPAD] = reinterpret_cast<float (*)[KC + WPAD]>(ws_raw);
-    __shared__ float logit[TT][EP + 1];
-
-    const int tid = threadIdx.x;
-    const int t0 = blockIdx.x * TT;
-    const int e = tid % EP;
-    const int grp = tid / EP;
-
-    float acc[TT];
+// W [E, d] fp32 -> planes in matrix-core operand order:
+// [(expert sub-tile st, k step kk, plane p)][lane = half*32 + row][8 bf16], lane's 8 columns = kk*16 + half*8 + 0..7
+__global__ __launch_bounds__(256) void split_router_weights(const float* __restrict__ W, int E, int E_pad, int d,
+                                                            uint16_t* __restrict__ planes) {
+    const int groups = d / 8;
+    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (int64_t)E_pad * groups) return;
+    const int e = (int)(idx / groups), g = (int)(idx % groups);
+    float w[8];
 #pragma unroll
-    for (int t = 0; t < TT; ++t) acc[t] = 0.f;
-
-    for (int kc = 0; kc < d; kc += KC) {
-        // activations: TT x KC bf16 = TT*KC/8 vectors of 8
-        if (tid < TT * KC / 8) {
-            const int t = tid / (KC / 8), c8 = tid % (KC / 8);
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (t0 + t < T) v = *reinterpret_cast<const uint4*>(x + (size_t)(t0 + t) * d + kc + c8 * 8);
-            float* dst = &xs[t][c8 * 8];
-            dst[0] = bf16_to_f32(v.x & 0xFFFF); dst[1] = bf16_to_f32(v.x >> 16);
-            dst[2] = bf16_to_f32(v.y & 0xFFFF); dst[3] = bf16_to_f32(v.y >> 16);
-            dst[4] = bf16_to_f32(v.z & 0xFFFF); dst[5] = bf16_to_f32(v.z >> 16);
-            dst[6] = bf16_to_f32(v.w & 0xFFFF); dst[7] = bf16_to_f32(v.w >> 16);
-        }
-        // router weights: EP x KC floats, coalesced along the hidden axis
-        for (int i = tid; i < EP * (KC / 4); i += 256) {
-            const int r = i / (KC / 4), c4 = i % (KC / 4);
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (r < E) v = *reinterpret_cast<const float4*>(W + (size_t)r * d + kc + c4 * 4);
-            *reinterpret_cast<float4*>(&ws[r][c4 * 4]) = v;
-        }
-        __syncthreads();
-#pragma unroll
-        for (int cc = 0; cc < CPG; cc += 4) {
-            const int c = grp * CPG + cc;
-            const float4 w4 = *reinterpret_cast<const float4*>(&ws[e][c]);
-#pragma unroll
-            for (int t = 0; t < TT; ++t) {
-                const float4 x4 = *reinterpret_cast<const float4*>(&xs[t][c]);
-                float a = acc[t];
-                a = fmaf(x4.x, w4.x, a);
-                a = fmaf(x4.y, w4.y, a);
-                a = fmaf(x4.z, w4.z, a);
-                a = fmaf(x4.w, w4.w, a);
-                acc[t] = a;
-            }
-        }
-        __syncthreads();
+    for (int j = 0; j < 8; ++j) w[j] = 0.f;
+    if (e < E) {
+        const float4 a = *reinterpret_cast<const float4*>(W + (size_t)e * d + g * 8);
+        const float4 b = *reinterpret_cast<const float4*>(W + (size_t)e * d + g * 8 + 4);
+        w[0] = a.x; w[1] = a.y; w[2] = a.z; w[3] = a.w; w[4] = b.x; w[5] = b.y; w[6] = b.z; w[7] = b.w;
     }
+    uint32_t p[3][8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const uint32_t h0 = f32_to_bf16_rne_bits(w[j]);
+        const float r1 = w[j] - bf16_bits_to_f32(h0);          // exact
+        const uint32_t h1 = f32_to_bf16_rne_bits(r1);
+        const float r2 = r1 - bf16_bits_to_f32(h1);            // exact, at most 8 significant bits left
+        p[0][j] = h0; p[1][j] = h1; p[2][j] = f32_to_bf16_rne_bits(r2);
+    }
+    const int st = e >> 5, row = e & 31, kk = g >> 1, half = g & 1;
+    const int nk = d / 16;
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) {
+        uint4 v;
+        v.x = p[pl][0] | (p[pl][1] << 16); v.y = p[pl][2] | (p[pl][3] << 16);
+        v.z = p[pl][4] | (p[pl][5] << 16); v.w = p[pl][6] | (p[pl][7] << 16);
+        const size_t off = ((((size_t)st * nk + kk) * 3 + pl) * 64 + half * 32 + row) * 8;
+        *reinterpret_cast<uint4*>(planes + off) = v;
+    }
+}
 
-    if (GRP == 1) {
+// NS: 32-expert sub-tiles per wave (E_pad = 128*NS)
+template <int NS>
+__global__ __launch_bounds__(256, 2) void route_mfma_kernel(const uint16_t* __restrict__ x,
+                                                            const uint16_t* __restrict__ planes,
+                                                            const float* __restrict__ bias, int T, int d, int E,
+                                                            int k, int32_t* __restrict__ topk_idx,
+                                                            float* __restrict__ topk_w) {
+    // two activation stages of 128 rows x 128 bytes; the candidate lists [token][wave][MAX_K]
+    // of {logit, expert id} reuse the storage afterwards
+    __shared__ __attribute__((aligned(16))) uint8_t smem[RT * 4 * MAX_K * 8];
+    static_assert(RT * 4 * MAX_K * 8 >= 2 * RT * 128, "stages fit");
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, half = lane >> 5;
+    const int t0 = blockIdx.x * RT;
+    const int nk = d / 16, nchunks = d / RKC;
+
+    // activation staging: thread owns 16-byte chunk (row, c) for 4 rows
+    const int xc = tid & 7, xr = tid >> 3;
+    const uint16_t* xsrc[4];
+    uint32_t xdst[4];
 #pragma unroll
-        for (int t = 0; t < TT; ++t) logit[t][e] = acc[t];
-    } else {
-        float* part = ws_raw;                         // [GRP][TT][EP]
+    for (int i = 0; i < 4; ++i) {
+        const int row = xr + 32 * i;
+        const int t = min(t0 + row, T - 1);
+        xsrc[i] = x + (size_t)t * d + xc * 8;
+        xdst[i] = row * 128 + ((xc ^ (row & 7)) << 4);
+    }
+    const uint4* wsrc[NS];
 #pragma unroll
-        for (int t = 0; t < TT; ++t) part[(grp * TT + t) * EP + e] = acc[t];
+    for (int s = 0; s < NS; ++s)
+        wsrc[s] = reinterpret_cast<const uint4*>(planes) + ((size_t)(wave * NS + s) * nk * 3) * 64 + lane;
+
+    v16f acc[NS][4];
+#pragma unroll
+    for (int s = 0; s < NS; ++s)
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[s][ts][r] = 0.f;
+
+    uint4 xreg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) xreg[i] = *reinterpret_cast<const uint4*>(xsrc[i]);
+
+    for (int kc = 0; kc < nchunks; ++kc) {
+        uint8_t* stage = smem + (kc & 1) * RT * 128;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(stage + xdst[i]) = xreg[i];
         __syncthreads();
-        for (int i = tid; i < TT * EP; i += 256) {
-            const int t = i / EP, ee = i % EP;
-            float s = 0.f;
-            for (int g = 0; g < GRP; ++g) s += part[(g * TT + t) * EP + ee];
-            logit[t][ee] = s;
+        if (kc + 1 < nchunks) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) xreg[i] = *reinterpret_cast<const uint4*>(xsrc[i] + (size_t)(kc + 1) * RKC);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int kk = kc * 4 + ks;
+            uint4 a[NS][3];
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+#pragma unroll
+                for (int p = 0; p < 3; ++p) a[s][p] = wsrc[s][((size_t)kk * 3 + p) * 64];
+            uint4 b[4];
+#pragma unroll
+            for (int ts = 0; ts < 4; ++ts) {
+                const int row = ts * 32 + l32;
+                b[ts] = *reinterpret_cast<const uint4*>(stage + row * 128 + (((ks * 2 + half) ^ (row & 7)) << 4));
+            }
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+#pragma unroll
+                    for (int ts = 0; ts < 4; ++ts)
+                        acc[s][ts] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            __builtin_bit_cast(v8bf, a[s][p]), __builtin_bit_cast(v8bf, b[ts]), acc[s][ts], 0, 0, 0);
+        }
+    }
+    __syncthreads();                                           // all reads of the activation stages are done
+
+    // ---- per-wave top-k.  Lane (l32, half) holds, for token ts*32+l32, the logits of experts
+    //      wave*32*NS + s*32 + (r/4)*8 + half*4 + (r%4).  Candidates: cand[token][wave][j] = {logit, idx}
+    float2* cand = reinterpret_cast<float2*>(smem);
+    uint32_t taken[4] = {0u, 0u, 0u, 0u};                      // bit (s*16 + r)
+#pragma unroll
+    for (int ts = 0; ts < 4; ++ts) {
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int e = (wave * NS + s) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                if (e >= E) taken[ts] |= 1u << (s * 16 + r);
+            }
+    }
+    for (int j = 0; j < k; ++j) {
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) {
+            float bs = 0.f, bl = 0.f;
+            int bi = NO_CAND, bpos = 0;
+#pragma unroll
+            for (int s = 0; s < NS; ++s)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    // ascending expert index within the lane: (r>>2) major, (r&3) minor, s outermost
+                    const int e = (wave * NS + s) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                    const float lg = acc[s][ts][r];
+                    const float sc = lg + (bias ? bias[min(e, E - 1)] : 0.f);
+                    const bool free_ = !((taken[ts] >> (s * 16 + r)) & 1u);
+                    if (free_ && (bi == NO_CAND || sc > bs)) { bs = sc; bl = lg; bi = e; bpos = s * 16 + r; }
+                }
+            // the partner lane holds the other half of the wave's experts for the same token
+            const float os = __shfl_xor(bs, 32);
+            const float ol = __shfl_xor(bl, 32);
+            const int oi = __shfl_xor(bi, 32);
+            const bool mine = bi != NO_CAND && (oi == NO_CAND || bs > os || (bs == os && bi < oi));
+            if (mine) taken[ts] |= 1u << bpos;
+            if (half == 0) {
+                float2 c;
+                c.x = mine ? bl : ol;
+                c.y = __int_as_float(mine ? bi : oi);
+                cand[((ts * 32 + l32) * 4 + wave) * MAX_K + j] = c;
+            }
         }
     }
     __syncthreads();
 
-    // ---- top-k and gate weights: one wave per token, four tokens in flight ----
-    const int lane = tid & 63, wave = tid >> 6;
-    for (int t = wave; t < TT; t += 4) {
-        if (t0 + t >= T) break;                       // uniform per wave
-        float sc[VPT];
-        bool taken[VPT];
-#pragma unroll
-        for (int v = 0; v < VPT; ++v) {
-            const int ee = lane + 64 * v;
-            taken[v] = !(ee < E);
-            sc[v] = 0.f;
-            if (ee < E) sc[v] = logit[t][ee] + (bias ? bias[ee] : 0.f);
-        }
-        int my_idx = 0;
-        float my_logit = 0.f;
+    // ---- merge the four waves' candidates, softmax, store: one thread per token
+    if (tid < RT && t0 + tid < T) {
+        const float2* mine = cand + (size_t)tid * 4 * MAX_K;
+        uint64_t used = 0ull;
+        float sel_logit[MAX_K];
+        int sel_idx[MAX_K];
+        float m = -INFINITY;
         for (int j = 0; j < k; ++j) {
-            float bs = 0.f;
-            int bi = 0x7FFFFFFF;                      // "no candidate"
-#pragma unroll
-            for (int v = 0; v < VPT; ++v) {
-                const int ee = lane + 64 * v;
-                if (!taken[v] && (bi == 0x7FFFFFFF || sc[v] > bs)) { bs = sc[v]; bi = ee; }
+            float bs = 0.f, bl = 0.f;
+            int bi = NO_CAND, bq = 0;
+            for (int q = 0; q < 4 * MAX_K; ++q) {
+                if ((q & (MAX_K - 1)) >= k || ((used >> q) & 1ull)) continue;
+                const float2 c = mine[q];
+                const int e = __float_as_int(c.y);
+                if (e == NO_CAND) continue;
+                const float sc = c.x + (bias ? bias[e] : 0.f);
+                if (bi == NO_CAND || sc > bs || (sc == bs && e < bi)) { bs = sc; bl = c.x; bi = e; bq = q; }
             }
-#pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) {
-                const float os = __shfl_xor(bs, off);
-                const int oi = __shfl_xor(bi, off);
-                const bool other_valid = oi != 0x7FFFFFFF;
-                const bool mine_valid = bi != 0x7FFFFFFF;
-                const bool take = other_valid && (!mine_valid || os > bs || (os == bs && oi < bi));
-                if (take) { bs = os; bi = oi; }
-            }
-            // bi is now uniform across the wave
-#pragma unroll
-            for (int v = 0; v < VPT; ++v)
-                if (lane + 64 * v == bi) taken[v] = true;
-            if (lane == j) { my_idx = bi; my_logit = logit[t][bi]; }
+            used |= 1ull << bq;
+            sel_logit[j] = bl;
+            sel_idx[j] = bi;
+            m = fmaxf(m, bl);
         }
-        // softmax over the k selected unbiased logits (lanes 0..k-1)
-        float m = (lane < k) ? my_logit : -INFINITY;
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) m = fmaxf(m, __shfl_xor(m, off));
-        float p = (lane < k) ? expf(my_logit - m) : 0.f;
-        float s = p;
-#pragma unroll
-        for (int off = 8; off >= 1; off >>= 1) s += __shfl_xor(s, off);
-        if (lane < k) {
-            topk_idx[(size_t)(t0 + t) * k + lane] = my_idx;
-            topk_w[(size_t)(t0 + t) * k + lane] = p / s;
+        float sum = 0.f;
+        for (int j = 0; j < k; ++j) { sel_logit[j] = expf(sel_logit[j] - m); sum += sel_logit[j]; }
+        for (int j = 0; j < k; ++j) {
+            topk_idx[(size_t)(t0 + tid) * k + j] = sel_idx[j];
+            topk_w[(size_t)(t0 + tid) * k + j] = sel_logit[j] / sum;
         }
     }
 }
 
 }  // namespace
 
+size_t route_workspace_bytes(int E, int d) {
+    const int E_pad = E <= 128 ? 128 : 256;
+    return (size_t)3 * E_pad * d * sizeof(uint16_t);
+}
+
 hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const float* bias,
                         int32_t* topk_idx, float* topk_w) {
     const moe_dims& D = c->dims;
     if (D.T == 0) return hipSuccess;
-    const int grid = (D.T + TT - 1) / TT;
-#define ROUTE_CASE(EP)                                                                           \
-    hipLaunchKernelGGL((route_kernel<EP>), dim3(grid), dim3(256), 0, c->stream, x, W_r, bias, D.T, \
-                       D.d, D.E, D.k, topk_idx, topk_w)
-    if (D.E <= 32) ROUTE_CASE(32);
-    else if (D.E <= 64) ROUTE_CASE(64);
-    else if (D.E <= 128) ROUTE_CASE(128);
-    else ROUTE_CASE(256);
-#undef ROUTE_CASE
+    const int E_pad = D.E <= 128 ? 128 : 256;
+    const int64_t nthreads = (int64_t)E_pad * (D.d / 8);
+    hipLaunchKernelGGL(split_router_weights, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, c->stream,
+                       W_r, D.E, E_pad, D.d, c->router_planes);
+    const int grid = (D.T + RT - 1) / RT;
+    if (E_pad == 128)
+        hipLaunchKernelGGL((route_mfma_kernel<1>), dim3(grid), dim3(256), 0, c->stream, x, c->router_planes, bias,
+                           D.T, D.d, D.E, D.k, topk_idx, topk_w);
+    else
+        hipLaunchKernelGGL((route_mfma_kernel<2>), dim3(grid), dim3(256), 0, c->stream, x, c->router_planes, bias,
+                           D.T, D.d, D.E, D.k, topk_idx, topk_w);
     return hipGetLastError();
 }
 
