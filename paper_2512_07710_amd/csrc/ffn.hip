@@ -43,35 +43,56 @@ constexpr int NXCD = 8;
 struct Work { int32_t expert; int32_t row0; int32_t ft; };
 
 // ------------------------------------------------------------------ work list
-// One thread per expert: its row tiles x feature tiles, row tile fastest.
+// One thread per expert.  Full 256-row tiles of all experts come first, ordered (expert,
+// feature tile, row tile); the ragged last tiles follow, ordered (expert, feature tile).
+// Units that share a weight tile or an activation tile are thus neighbours AND do the same
+// amount of work, so the blocks that run them side by side on one XCD advance in step and
+// hit each other's lines in that XCD's L2 (a few K steps of skew already exceed what the L2
+// retains, and the shared tile is then fetched again from HBM).
 __global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ offsets, int E, int n_ft,
                                                   Work* __restrict__ work, int32_t* __restrict__ n_work) {
-    __shared__ int32_t s_n[MAX_E];
+    __shared__ int32_t s_full[MAX_E];
+    __shared__ int32_t s_tail[MAX_E];
     const int tid = threadIdx.x;
     int start = 0, cnt = 0;
     if (tid < E) {
         start = offsets[tid];
         cnt = offsets[tid + 1] - start;
     }
-    const int tiles = (cnt + TOK_TILE - 1) / TOK_TILE;
-    s_n[tid] = tiles;
+    const int full = cnt / TOK_TILE;
+    const int tail = (cnt % TOK_TILE) ? 1 : 0;
+    s_full[tid] = full;
+    s_tail[tid] = tail;
     __syncthreads();
     for (int off = 1; off < MAX_E; off <<= 1) {
-        int add = (tid >= off) ? s_n[tid - off] : 0;
+        const int a = (tid >= off) ? s_full[tid - off] : 0;
+        const int b = (tid >= off) ? s_tail[tid - off] : 0;
         __syncthreads();
-        s_n[tid] += add;
+        s_full[tid] += a;
+        s_tail[tid] += b;
         __syncthreads();
     }
-    const int base = (s_n[tid] - tiles) * n_ft;
+    const int all_full = s_full[MAX_E - 1];
+    const int base_full = (s_full[tid] - full) * n_ft;
     for (int f = 0; f < n_ft; ++f)
-        for (int i = 0; i < tiles; ++i) {
+        for (int i = 0; i < full; ++i) {
             Work w;
             w.expert = tid;
             w.row0 = start + i * TOK_TILE;
             w.ft = f;
-            work[base + f * tiles + i] = w;
+            work[base_full + f * full + i] = w;
         }
-    if (tid == MAX_E - 1) *n_work = s_n[tid] * n_ft;
+    if (tail) {
+        const int base_tail = (all_full + s_tail[tid] - 1) * n_ft;
+        for (int f = 0; f < n_ft; ++f) {
+            Work w;
+            w.expert = tid;
+            w.row0 = start + full * TOK_TILE;
+            w.ft = f;
+            work[base_tail + f] = w;
+        }
+    }
+    if (tid == MAX_E - 1) *n_work = (all_full + s_tail[tid]) * n_ft;
 }
 
 // ------------------------------------------------------------------ helpers
