@@ -50,7 +50,7 @@ typedef struct {
 
 /* Create a context for one layer shape.  Allocates the internal device workspace
  * (chunk histograms, the tile work list, and the quantised hidden activations
- * hq [N,F] u8 + hs [N,F/128] f32).  hip_stream is a hipStream_t (NULL = default
+ * hq [N,F] u8 + hs [F/128][N] f32).  hip_stream is a hipStream_t (NULL = default
  * stream).  The device current at creation must be current at every later call. */
 int moe_create(moe_ctx** out, const moe_dims* dims, void* hip_stream);
 int moe_destroy(moe_ctx* ctx);
@@ -94,8 +94,11 @@ int moe_check_ids(moe_ctx* ctx);
  * Otherwise output rows dst_rows[r*fanout + j], j < fanout, all receive the
  * quantised input row r (pass inv_perm and fanout = k to build the expert-ordered
  * activation matrix in one pass over x).
- *   x_bf16 [rows_in, cols]; q [rows_in*fanout, cols] u8;
- *   scales [rows_in*fanout, cols/128] f32.  cols must be a multiple of 128.
+ *   x_bf16 [rows_in, cols]; q [rows_out, cols] u8 with rows_out = rows_in*fanout;
+ *   scales [cols/128][rows_out] f32, group-major: the scale of output row p and
+ *   column group g is scales[g*rows_out + p] (one contiguous plane per 128-column
+ *   block, the order in which the grouped GEMM walks them).  cols must be a
+ *   multiple of 128.
  * Does not use the context's T/d: any rows_in >= 0 and cols are accepted. */
 int moe_quantize_fp8(moe_ctx* ctx, const uint16_t* x_bf16, int64_t rows_in, int32_t cols,
                      int32_t block, const int32_t* dst_rows, int32_t fanout,
@@ -103,14 +106,15 @@ int moe_quantize_fp8(moe_ctx* ctx, const uint16_t* x_bf16, int64_t rows_in, int3
 
 /* Grouped SwiGLU expert FFN on expert-sorted rows.  For expert e and rows
  * p in [offsets[e], offsets[e+1]):
- *   g[p,f] = sum_kb xs[p,kb]*s1[e,f/128,kb] * sum_{c in block kb} xq[p,c]*W1[e,f,c]
+ *   g[p,f] = sum_kb xs[kb,p]*s1[e,f/128,kb] * sum_{c in block kb} xq[p,c]*W1[e,f,c]
  *   u[p,f] = the same with W3, s3
  *   h = g/(1+exp(-g)) * u (fp32), quantised per row per 128 columns exactly like
  *       moe_quantize_fp8 -> hq, hs (kept in the context workspace)
- *   y_perm[p,c] = sum_fb hs[p,fb]*s2[e,c/128,fb] * sum_{f in block fb} hq[p,f]*W2[e,c,f]
+ *   y_perm[p,c] = sum_fb hs[fb,p]*s2[e,c/128,fb] * sum_{f in block fb} hq[p,f]*W2[e,c,f]
  * FP8 products are accumulated in fp32 on the matrix cores, one 128-wide block at
  * a time, and each block's partial sum is scaled in fp32.
- *   xq_perm [N,d] u8; xs_perm [N,d/128] f32; offsets [E+1] i32 (device);
+ *   xq_perm [N,d] u8; xs_perm [d/128][N] f32 (group-major, as moe_quantize_fp8 writes
+ *   it); offsets [E+1] i32 (device);
  *   W1,W3 [E,F,d] u8; W2 [E,d,F] u8; s1,s3 [E,F/128,d/128] f32; s2 [E,d/128,F/128] f32;
  *   y_perm [N,d] f32. */
 int moe_expert_ffn_fp8(moe_ctx* ctx, const uint8_t* xq_perm, const float* xs_perm,
@@ -126,7 +130,7 @@ int moe_combine(moe_ctx* ctx, const float* y_perm, const int32_t* inv_perm, cons
                 uint16_t* y_bf16);
 
 /* Device pointers to the hidden activations written by the last
- * moe_expert_ffn_fp8 call (hq [N,F] u8, hs [N,F/128] f32); valid until the
+ * moe_expert_ffn_fp8 call (hq [N,F] u8, hs [F/128][N] f32, group-major); valid until the
  * context is destroyed.  For stage-isolated checks. */
 int moe_debug_hidden(moe_ctx* ctx, const uint8_t** hq, const float** hs);
 

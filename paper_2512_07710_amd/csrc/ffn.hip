@@ -8,19 +8,20 @@
 //
 // Main loop, one iteration per 128-wide K block (= one scale block):
 //   * both operand tiles are copied global -> LDS by direct-to-LDS loads (no staging
-//     registers), double buffered, 16-byte chunks XOR-swizzled by row so that the 32-row
-//     operand reads are bank-conflict free;
+//     registers) into rings of three (weights) and two (activations) 32 KiB buffers, 16-byte
+//     chunks XOR-swizzled by row so that the 32-row operand reads spread over all 64 banks;
 //   * partial = W_tile * X_tile^T with two v_mfma_f32_32x32x64_f8f6f4 per 32x32 sub-tile;
-//   * acc += (xs[row,kb] * ws[feature block,kb]) * partial in fp32.
+//   * acc += (xs[kb][row] * ws[feature block,kb]) * partial in fp32.
 // The product is taken as (features x tokens): in the 32x32 accumulator layout a lane then
 // owns ONE token column and 16 feature rows, so the activation scale is one scalar per lane
 // and sub-tile, and the 128-wide amax of the epilogue is a lane-local reduction plus one
 // cross-half shuffle and one exchange between the two waves that share a token.
+// Activation scales are K-block major ([K/128][rows]): the 32 lanes of a half-wave read 32
+// consecutive floats of one plane.
 //
 // Eight waves per block: wave (wt, wf) owns 64 tokens x 128 staged weight rows (2 x 4
-// sub-tiles): 6 operand sub-tiles feed 8 MFMA pairs, which keeps LDS reads under the
-// 128 B/clk the LDS delivers.  Waves whose 64 tokens lie beyond the expert's last row skip
-// their MFMAs, so a ragged tail costs a fraction of a tile.
+// sub-tiles): 6 operand sub-tiles feed 8 MFMA pairs.  Waves whose 64 tokens lie beyond the
+// expert's last row skip their MFMAs, so a ragged tail costs a fraction of a tile.
 //
 // GEMM1: staged rows of wave wf are [64 gate rows | 64 up rows] of the same features;
 //        epilogue h = silu(g)*u, re-quantised to e4m3 with one scale per (row, 128 features).
@@ -36,7 +37,10 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 constexpr int KB = QBLOCK;                        // K bytes per stage (= one scale block)
 constexpr int W_ROWS = 256;                       // staged weight rows per block
 constexpr int X_ROWS = TOK_TILE;                  // staged activation rows per block (256)
-constexpr int STAGE_BYTES = (W_ROWS + X_ROWS) * KB;   // 64 KiB
+constexpr int W_TILE = W_ROWS * KB;                // 32 KiB: one K block of the weight tile
+constexpr int X_TILE = X_ROWS * KB;                // 32 KiB: one K block of the activation tile
+constexpr int NW_BUF = 3, NX_BUF = 2;              // LDS ring depths
+constexpr int X_RING = NW_BUF * W_TILE;            // byte offset of the activation ring
 constexpr int NTHREADS = 512;
 constexpr int NXCD = 8;
 
@@ -96,19 +100,6 @@ __global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ of
 }
 
 // ------------------------------------------------------------------ helpers
-__device__ inline int swz(int row, int chunk) { return row * KB + ((chunk ^ (row & 7)) << 4); }
-
-// the 32 K-bytes a lane feeds to one 32x32x64 MFMA: row `row`, K half `half` of K step `ks`
-__device__ inline v8i load_operand(const uint8_t* tile, int row, int ks, int half) {
-    const int c0 = ks * 4 + half * 2;
-    const uint4 lo = *reinterpret_cast<const uint4*>(tile + swz(row, c0));
-    const uint4 hi = *reinterpret_cast<const uint4*>(tile + swz(row, c0 + 1));
-    v8i r;
-    r[0] = lo.x; r[1] = lo.y; r[2] = lo.z; r[3] = lo.w;
-    r[4] = hi.x; r[5] = hi.y; r[6] = hi.z; r[7] = hi.w;
-    return r;
-}
-
 // Direct global -> LDS copies.  Lane i of the wave deposits its bytes at lds_addr + i*size;
 // the global address is sbase + voff (per lane).  Completion is tracked by vmcnt; the
 // compiler does not see these as memory operations of its own, so every wait on them is
@@ -117,9 +108,27 @@ __device__ inline void dma16(uint32_t lds_addr, uint32_t voff, const void* sbase
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                  :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
 }
-__device__ inline void dma4(uint32_t lds_addr, uint32_t voff, const void* sbase) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
-                 :: "s"(lds_addr), "v"(voff), "s"(sbase) : "memory");
+
+// The matrix instructions are written as volatile asm so that they stay exactly where the
+// source puts them: the schedule below relies on it.  T = A*B (first K half) and T += A*B.
+__device__ inline void mfma_first(v16f& t, const v8i& a, const v8i& b) {
+    asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, 0" : "=&v"(t) : "v"(a), "v"(b) : "memory");
+}
+__device__ inline void mfma_acc(v16f& t, const v8i& a, const v8i& b) {
+    asm volatile("v_mfma_f32_32x32x64_f8f6f4 %0, %1, %2, %0" : "+v"(t) : "v"(a), "v"(b) : "memory");
+}
+// An empty volatile asm that "rewrites" x: uses of x after it cannot move above it, and
+// values feeding x cannot move below it.
+#define PIN(x) asm volatile("" : "+v"(x))
+
+// the 32 K-bytes a lane feeds to one 32x32x64 MFMA, from a row's two swizzled 16-byte chunks
+__device__ inline v8i lds_operand(const uint8_t* row, uint32_t o0, uint32_t o1) {
+    const uint4 lo = *reinterpret_cast<const uint4*>(row + o0);
+    const uint4 hi = *reinterpret_cast<const uint4*>(row + o1);
+    v8i r;
+    r[0] = lo.x; r[1] = lo.y; r[2] = lo.z; r[3] = lo.w;
+    r[4] = hi.x; r[5] = hi.y; r[6] = hi.z; r[7] = hi.w;
+    return r;
 }
 
 __device__ inline float clamp448(float v) { return fminf(fmaxf(v, -448.f), 448.f); }
@@ -134,10 +143,10 @@ __device__ inline uint32_t pack4_e4m3(float a, float b, float c, float d) {
 // ------------------------------------------------------------------ GEMM kernel
 // GATED = true : Wa = W1, Wb = W3 [E, NOUT, K]; feature tile = 128 features (gate + up rows)
 // GATED = false: Wa = W2 [E, NOUT, K]; feature tile = 256 output features
-// act [N, K] u8 and act_s [N, K/128] f32 are the expert-sorted activations and their scales.
+// act [N, K] u8 are the expert-sorted activations; act_s [K/128][N] f32 their scales, K-block major.
 template <bool GATED>
 __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restrict__ act,
-                                                        const float* __restrict__ act_s,
+                                                        const float* __restrict__ act_s, int n_rows,
                                                         const int32_t* __restrict__ offsets,
                                                         const Work* __restrict__ work,
                                                         const int32_t* __restrict__ n_work,
@@ -149,10 +158,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                                                         float* __restrict__ y_perm) {
     constexpr int FT = GATED ? 128 : 256;                      // output features per tile
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-    // [2 stages][W rows | X rows][128 B], then [2][256] activation scales, [256] dummy, [2][256] amax
-    uint8_t* const s_stage = smem;
-    float* const s_xs = reinterpret_cast<float*>(smem + 2 * STAGE_BYTES);
-    float* const s_amax = s_xs + 3 * X_ROWS;
+    // [3][256 weight rows][128 B] then [2][256 activation rows][128 B]: all 160 KiB.  The amax
+    // exchange of the epilogue reuses the first bytes once the main loop is over.
+    float* const s_amax = reinterpret_cast<float*>(smem);
 
     // ---- which work unit: XCD x (= blockIdx % 8) walks the contiguous range [x*chunk, (x+1)*chunk)
     const int total = *n_work;
@@ -173,57 +181,42 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     const int nkb = K / KB;
     const int nblk_out = NOUT / QBLOCK;
 
-    // ---- DMA plan: wave w copies staged rows [w*64, w*64+64) of the 512 (W rows then X rows),
-    //      8 instructions of 8 rows each; lane i -> row i/8, LDS chunk slot i%8.
-    const uint8_t* dma_base;                                   // wave-uniform
-    uint32_t dma_off[8];
+    // ---- copy plan: wave w brings staged weight rows [32w, 32w+32) and staged activation rows
+    //      [32w, 32w+32) of every K block, 4 + 4 instructions of 8 rows each; lane i -> row i/8,
+    //      LDS chunk slot i%8 which receives global chunk slot ^ (row & 7) ^ ((row >> 3) & 1): with that
+    //      swizzle the 32-row x 16-byte operand reads below touch all 64 LDS banks evenly.
+    //      Staged weight row r: GATED: features f0 + (r/128)*64 + r%64, gate (Wa) if (r/64)%2 == 0 else up (Wb).
+    const uint8_t* w_base;                                     // wave-uniform
+    uint32_t w_off[4], x_off[4];
     {
         const int sub = lane >> 3, cslot = lane & 7;
-        if (wave < 4) {
-            // staged W row r: GATED: wave 0,2 gate rows, wave 1,3 up rows of features f0 + (r/128)*64 + r%64
-            const int r0 = wave * 64;
-            const uint8_t* wbase = (GATED && (wave & 1)) ? Wb : Wa;
-            dma_base = wbase + (size_t)e * NOUT * (size_t)K;
+        const uint8_t* wmat = (GATED && ((wave >> 1) & 1)) ? Wb : Wa;
+        w_base = wmat + (size_t)e * NOUT * (size_t)K;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = r0 + j * 8 + sub;
-                int f = GATED ? f0 + (r >> 7) * 64 + (r & 63) : f0 + r;
-                f = min(f, NOUT - 1);
-                dma_off[j] = (uint32_t)f * (uint32_t)K + ((cslot ^ (r & 7)) << 4);
-            }
-        } else {
-            const int r0 = (wave - 4) * 64;
-            dma_base = act;
-            // rows past the expert's segment repeat its last row (never stored)
-            const size_t first = (size_t)wk.row0 * K;
-            dma_base += first;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const int r = r0 + j * 8 + sub;
-                const int p = min(wk.row0 + r, row_end - 1) - wk.row0;
-                dma_off[j] = (uint32_t)p * (uint32_t)K + ((cslot ^ (r & 7)) << 4);
-            }
+        for (int j = 0; j < 4; ++j) {
+            const int r = wave * 32 + j * 8 + sub;
+            int f = GATED ? f0 + (r >> 7) * 64 + (r & 63) : f0 + r;
+            f = min(f, NOUT - 1);
+            w_off[j] = (uint32_t)f * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
+            const int p = min(wk.row0 + r, row_end - 1) - wk.row0;      // rows past the segment repeat its last row
+            x_off[j] = (uint32_t)p * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
         }
     }
-    // activation scales of one K block: waves 4..7 copy 64 each; waves 0..3 issue a same-sized
-    // copy into a dummy area so that every wave has the same number of copies in flight
-    const float* xs_base = act_s + (size_t)wk.row0 * nkb;
-    uint32_t xs_off;
-    {
-        const int r = ((wave & 3) * 64 + lane);
-        const int p = min(wk.row0 + r, row_end - 1) - wk.row0;
-        xs_off = (uint32_t)p * (uint32_t)nkb * 4u;
-    }
+    const uint8_t* x_base = act + (size_t)wk.row0 * K;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
-    const uint32_t lds_rows = lds0 + wave * 64 * KB;           // this wave's rows inside a stage
-    const uint32_t lds_xs = lds0 + 2 * STAGE_BYTES + (wave >= 4 ? 0 : 2 * X_ROWS * 4) + (wave & 3) * 64 * 4;
+    const uint32_t lds_rows = lds0 + wave * 32 * KB;           // this wave's rows inside a tile buffer
 
-    auto issue_stage = [&](int kb, int buf) {
-        const uint8_t* src = dma_base + (size_t)kb * KB;
-        const uint32_t dst = lds_rows + buf * STAGE_BYTES;
+    auto issue_w = [&](int kb, int wslot) {
+        const uint8_t* src = w_base + (size_t)kb * KB;
+        const uint32_t dst = lds_rows + wslot * W_TILE;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) dma16(dst + j * 8 * KB, dma_off[j], src);
-        dma4(lds_xs + (wave >= 4 ? buf * X_ROWS * 4 : 0), xs_off, xs_base + kb);
+        for (int j = 0; j < 4; ++j) dma16(dst + j * 8 * KB, w_off[j], src);
+    };
+    auto issue_x = [&](int kb, int xslot) {
+        const uint8_t* src = x_base + (size_t)kb * KB;
+        const uint32_t dst = lds_rows + X_RING + xslot * X_TILE;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dma16(dst + j * 8 * KB, x_off[j], src);
     };
 
     // ---- weight scales of this wave's rows (wave-uniform -> scalar loads)
@@ -241,69 +234,177 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[s][ts][r] = 0.f;
 
-    float wsa_next = sa_e[0], wsb_next = sb_e[0];
-    issue_stage(0, 0);
-    for (int kb = 0; kb < nkb; ++kb) {
-        const int buf = kb & 1;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");       // this wave's copies of stage kb landed
-        __builtin_amdgcn_s_barrier();                          // everybody's landed; stage kb-1 fully consumed
+    // Pipeline.  K block kb of the weight tile lives in ring slot kb % 3, of the activation tile in
+    // slot kb % 2.  Each wave passes ONE barrier per K block, placed after its last LDS read of block
+    // kb (before sub-tile product 6 of 8).  Behind that barrier block kb+1 is complete in LDS and the
+    // slots of block kb are free: the copies of activation block kb+2 and weight block kb+3 are
+    // issued there (always in that order, so that "all but the newest four copies have landed" is
+    // exactly "everything but the weight block two steps ahead"), and products 6 and 7 already fetch
+    // the first operands of block kb+1 into registers.
+    issue_x(0, 0);
+    issue_w(0, 0);
+    if (!wave_active) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (kb + 1 < nkb) issue_stage(kb + 1, buf ^ 1);
-        if (wave_active) {
-            const uint8_t* sW = s_stage + buf * STAGE_BYTES;
-            const uint8_t* sX = sW + W_ROWS * KB;
-            const float wsa = wsa_next, wsb = wsb_next;        // loaded one iteration ahead
-            if (kb + 1 < nkb) {
-                wsa_next = sa_e[kb + 1];
-                wsb_next = sb_e[kb + 1];
-            }
-            v8i b[2][2];
-            float sc_a[2], sc_b[2];
+        if (nkb > 1) { issue_x(1, 1); issue_w(1, 1); }
+        if (nkb > 2) issue_w(2, 2);
+        int wslot = 0;
+        for (int kb = 0; kb < nkb; ++kb) {
+            if (kb + 2 < nkb) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            if (kb + 2 < nkb) issue_x(kb + 2, kb & 1);
+            if (kb + 3 < nkb) issue_w(kb + 3, wslot);
+            wslot = (wslot == NW_BUF - 1) ? 0 : wslot + 1;
+        }
+    } else {
+        // per-lane constants of the operand reads
+        uint32_t offk[2][2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                offk[ks][j] = (uint32_t)(((ks * 4 + half * 2 + j) ^ (l32 & 7) ^ ((l32 >> 3) & 1)) << 4);
+        const uint32_t a_row = (uint32_t)(wf * 128 + l32) * KB;
+        const uint32_t b_row = (uint32_t)(X_RING + (wt * 64 + l32) * KB);
+        // activation scales of this lane's two token columns (K-block major: one plane per K block)
+        uint32_t xs_i[2];                                      // byte offset of the lane's row inside a plane
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) xs_i[ts] = 4u * (uint32_t)min(wk.row0 + wt * 64 + ts * 32 + l32, n_rows - 1);
+        const size_t plane = (size_t)n_rows * 4;
+        // issued as asm (saddr + 32-bit lane offset); the data is only touched behind a vmcnt wait
+        auto xs_load = [&](float& dst, int kb, int ts) {
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(xs_i[ts]),
+                         "s"(reinterpret_cast<const uint8_t*>(act_s) + (size_t)kb * plane) : "memory");
+        };
+        float xs_n[2];
+        xs_load(xs_n[0], 0, 0);
+        xs_load(xs_n[1], 0, 1);
+        float xs_cur[2];
+
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) asm volatile("v_mov_b32 %0, %1" : "=v"(xs_cur[ts]) : "v"(xs_n[ts]));
+        if (nkb > 1) {
+            xs_load(xs_n[0], 1, 0);
+            xs_load(xs_n[1], 1, 1);
+            issue_x(1, 1);
+            issue_w(1, 1);
+        }
+        if (nkb > 2) issue_w(2, 2);
+        v8i b[2][2], a[2][2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) a[0][ks] = lds_operand(smem + a_row, offk[ks][0], offk[ks][1]);
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                b[ts][ks] = lds_operand(smem + b_row + ts * 32 * KB, offk[ks][0], offk[ks][1]);
+        float sc[2][2];
+        {
+            const float wsa = sa_e[0], wsb = sb_e[0];
 #pragma unroll
             for (int ts = 0; ts < 2; ++ts) {
-                const int xrow = wt * 64 + ts * 32 + l32;
-                b[ts][0] = load_operand(sX, xrow, 0, half);
-                b[ts][1] = load_operand(sX, xrow, 1, half);
-                const float xsc = s_xs[buf * X_ROWS + xrow];
-                sc_a[ts] = xsc * wsa;
-                sc_b[ts] = xsc * wsb;
-            }
-            // Software pipeline over the 8 (weight sub-tile s, token sub-tile ts) pairs: the two
-            // MFMAs of pair i are issued before the 16 scale-FMAs of pair i-1, so the matrix
-            // pipe works on pair i while the vector ALU folds pair i-1 into the accumulators.
-            const int wrow0 = wf * 128 + l32;
-            v8i a0 = load_operand(sW, wrow0, 0, half);
-            v8i a1 = load_operand(sW, wrow0, 1, half);
-            v16f zero;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-            v16f prev = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, b[0][0], zero, 0, 0, 0, 0, 0, 0);
-            prev = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, b[0][1], prev, 0, 0, 0, 0, 0, 0);
-#pragma unroll
-            for (int i = 1; i < 8; ++i) {
-                const int s = i >> 1, ts = i & 1;
-                if (ts == 0) {
-                    a0 = load_operand(sW, wrow0 + s * 32, 0, half);
-                    a1 = load_operand(sW, wrow0 + s * 32, 1, half);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                v16f cur = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a0, b[ts][0], zero, 0, 0, 0, 0, 0, 0);
-                cur = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a1, b[ts][1], cur, 0, 0, 0, 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                const int ps = (i - 1) >> 1, pts = (i - 1) & 1;
-                const float sc = (GATED && ps >= 2) ? sc_b[pts] : sc_a[pts];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[ps][pts][r] = fmaf(sc, prev[r], acc[ps][pts][r]);
-                __builtin_amdgcn_sched_barrier(0);
-                prev = cur;
-            }
-            {
-                const float sc = GATED ? sc_b[1] : sc_a[1];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) acc[3][1][r] = fmaf(sc, prev[r], acc[3][1][r]);
+                sc[ts][0] = xs_cur[ts] * wsa;
+                sc[ts][1] = xs_cur[ts] * wsb;
             }
         }
+        v16f T0, T1;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) { T0[r] = 0.f; T1[r] = 0.f; }
+        float sc_pend = 0.f;                                   // scale of the sub-tile product still held in T1
+
+        // fold product `PS, PTS` (held in T0 for PTS == 0, T1 for PTS == 1) into its accumulator
+#define FOLD(PS, PTS, SCV)                                                                      \
+        do {                                                                                    \
+            if ((PTS) == 0) {                                                                   \
+                PIN(T0);                                                                        \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r)                                  \
+                    acc[PS][0][r] = fmaf((SCV), T0[r], acc[PS][0][r]);                          \
+            } else {                                                                            \
+                PIN(T1);                                                                        \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r)                                  \
+                    acc[PS][1][r] = fmaf((SCV), T1[r], acc[PS][1][r]);                          \
+            }                                                                                   \
+            PIN(acc[PS][PTS]);                                                                  \
+        } while (0)
+
+        int wslot = 0;                                         // ring slot of weight block kb
+        for (int kb = 0; kb < nkb; ++kb) {
+            const int wnext = (wslot == NW_BUF - 1) ? 0 : wslot + 1;
+            const uint8_t* sW = smem + wslot * W_TILE + a_row;                   // block kb
+            const uint8_t* sWn = smem + wnext * W_TILE + a_row;                  // block kb+1
+            const uint8_t* sXn = smem + b_row + ((kb & 1) ^ 1) * X_TILE;         // block kb+1
+            const int kn = min(kb + 1, nkb - 1);
+            const float wsa_n = sa_e[kn], wsb_n = sb_e[kn];            // consumed at the end of this step
+            // Eight sub-tile products, two MFMAs each.  The 16 scale-FMAs of product i-1 sit behind the
+            // second MFMA of product i: by then its result has left the matrix pipe (two more MFMAs
+            // have been issued since), and the vector ALU works in the shadow of the MFMA just issued.
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int s = i >> 1, ts = i & 1;
+                if (i == 6) {
+                    // all of this wave's reads of block kb have been issued; wait for them and for the
+                    // copies that must be complete, then meet the other waves
+                    if (kb + 2 < nkb) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+                    else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    asm volatile("" ::: "memory");
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2) asm volatile("v_mov_b32 %0, %1" : "=v"(xs_cur[t2]) : "v"(xs_n[t2]));
+                }
+                if (ts == 0) mfma_first(T0, a[s & 1][0], b[0][0]); else mfma_first(T1, a[s & 1][0], b[1][0]);
+                if (ts == 0 && s < 3) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks)
+                        a[(s + 1) & 1][ks] = lds_operand(sW + (s + 1) * 32 * KB, offk[ks][0], offk[ks][1]);
+                }
+                if (i == 6) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) a[0][ks] = lds_operand(sWn, offk[ks][0], offk[ks][1]);
+                    if (kb + 2 < nkb) {
+                        xs_load(xs_n[0], kb + 2, 0);
+                        xs_load(xs_n[1], kb + 2, 1);
+                        issue_x(kb + 2, kb & 1);
+                    }
+                }
+                if (i == 7 && kb + 3 < nkb) issue_w(kb + 3, wslot);
+                if (ts == 0) mfma_acc(T0, a[s & 1][1], b[0][1]); else mfma_acc(T1, a[s & 1][1], b[1][1]);
+                if (i == 0) {
+                    FOLD(3, 1, sc_pend);
+                } else {
+                    const int ps = (i - 1) >> 1, pts = (i - 1) & 1;
+                    FOLD(ps, pts, sc[pts][(GATED && ps >= 2) ? 1 : 0]);
+                }
+                if (i == 6) {
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) b[0][ks] = lds_operand(sXn, offk[ks][0], offk[ks][1]);
+                }
+                if (i == 7) {
+                    sc_pend = sc[1][GATED ? 1 : 0];
+#pragma unroll
+                    for (int t2 = 0; t2 < 2; ++t2) {
+                        sc[t2][0] = xs_cur[t2] * wsa_n;
+                        sc[t2][1] = xs_cur[t2] * wsb_n;
+                    }
+#pragma unroll
+                    for (int ks = 0; ks < 2; ++ks) b[1][ks] = lds_operand(sXn + 32 * KB, offk[ks][0], offk[ks][1]);
+                }
+            }
+            wslot = wnext;
+        }
+        // the last product: wait out the matrix pipe, then fold it
+        asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+        FOLD(3, 1, sc_pend);
+#undef FOLD
     }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();                              // every wave is done with the operand rings
+    asm volatile("" ::: "memory");
 
     // ---- epilogue.  Accumulator (s, ts, r) of this lane belongs to token
     //      row0 + wt*64 + ts*32 + l32 and staged weight row wf*128 + s*32 + (r/4)*8 + half*4 + r%4.
@@ -347,7 +448,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                                                              h[ts][s][r4 * 4 + 2] / sc, h[ts][s][r4 * 4 + 3] / sc);
                             *reinterpret_cast<uint32_t*>(dst + s * 32 + r4 * 8) = code;
                         }
-                    if (half == 0 && wf == 0) hs[(size_t)p * nblk_out + wk.ft] = sc;
+                    if (half == 0 && wf == 0) hs[(size_t)wk.ft * n_rows + p] = sc;
                 }
             }
         }
@@ -376,7 +477,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     }
 }
 
-constexpr size_t SMEM_BYTES = 2 * STAGE_BYTES + 5 * X_ROWS * sizeof(float);
+constexpr size_t SMEM_BYTES = NW_BUF * W_TILE + NX_BUF * X_TILE;   // 160 KiB
 
 }  // namespace
 
@@ -410,12 +511,12 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, con
     hipLaunchKernelGGL(build_work, dim3(1), dim3(256), 0, c->stream, offsets, D.E, nft2, work2, n_work2);
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     const int grid1 = ((c->max_tiles * nft1 + NXCD - 1) / NXCD) * NXCD;
-    hipLaunchKernelGGL((ffn_gemm<true>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, offsets,
+    hipLaunchKernelGGL((ffn_gemm<true>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, (int)((int64_t)D.T * D.k), offsets,
                        work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq, c->hs, (float*)nullptr);
     if (ev) (void)hipEventRecord(ev[1], c->stream);
     const int grid2 = ((c->max_tiles * nft2 + NXCD - 1) / NXCD) * NXCD;
     hipLaunchKernelGGL((ffn_gemm<false>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq, c->hs,
-                       offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2, (const float*)nullptr, D.F,
+                       (int)((int64_t)D.T * D.k), offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2, (const float*)nullptr, D.F,
                        D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     return hipGetLastError();

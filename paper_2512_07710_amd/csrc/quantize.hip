@@ -4,7 +4,8 @@
 // Sixteen lanes own one 128-column group: each loads 8 bf16 (16 bytes), the group
 // maximum is reduced with four xor-shuffles, and scale = amax/448 and x/scale are
 // computed with correctly rounded fp32 division so the codes are reproducible bit
-// for bit.  The row is read once and written `fanout` times.
+// for bit.  The row is read once and written `fanout` times.  Scales are stored K-block
+// major, scales[group][output row]: the layout the grouped GEMM reads them in.
 #include "moe_internal.hpp"
 
 namespace moe355 {
@@ -27,7 +28,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t* __re
                                                             int cols, const int32_t* __restrict__ dst_rows,
                                                             int fanout, uint8_t* __restrict__ q,
                                                             float* __restrict__ scales) {
-    const int groups = cols / QBLOCK;
+    const int64_t rows_out = dst_rows ? rows_in * fanout : rows_in;
     const int vecs = cols / 8;                        // 16-byte vectors per row, a multiple of 16
     for (int64_t r = blockIdx.x; r < rows_in; r += gridDim.x) {
         const uint16_t* xr = x + r * cols;
@@ -52,7 +53,7 @@ __global__ __launch_bounds__(256) void quantize_rows_kernel(const uint16_t* __re
                 const int64_t orow = dst_rows ? (int64_t)dst_rows[r * fanout + j] : r;
                 if (orow < 0) continue;               // assignment skipped by the permutation
                 *reinterpret_cast<uint2*>(q + orow * cols + (size_t)v * 8) = codes;
-                if ((v & 15) == 0) scales[orow * groups + g] = s;
+                if ((v & 15) == 0) scales[(int64_t)g * rows_out + orow] = s;
             }
         }
     }

@@ -30,7 +30,7 @@ class MoELayer:
         self.perm = torch.empty((N,), dtype=torch.int32, device=dev)
         self.inv_perm = torch.empty((N,), dtype=torch.int32, device=dev)
         self.xq = torch.empty((N, d), dtype=torch.uint8, device=dev)
-        self.xs = torch.empty((N, d // 128), dtype=torch.float32, device=dev)
+        self.xs = torch.empty((d // 128, N), dtype=torch.float32, device=dev)   # group-major scale planes
         self.y_perm = torch.empty((N, d), dtype=torch.float32, device=dev)
         self.y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
 
@@ -80,11 +80,11 @@ class MoELayer:
         return self.y
 
     def hidden(self):
-        """Copies of (hq [N,F] u8, hs [N,F/128] f32) written by the last expert_ffn call."""
+        """Copies of (hq [N,F] u8, hs [F/128,N] f32, group-major) written by the last expert_ffn call."""
         a, b = B.moe_debug_hidden(self.ctx)
         N, F = max(self.N, 1), self.F
         hq = torch.empty((N, F), dtype=torch.uint8, device=self.device)
-        hs = torch.empty((N, F // 128), dtype=torch.float32, device=self.device)
+        hs = torch.empty((F // 128, N), dtype=torch.float32, device=self.device)
         rt = ctypes.CDLL("libamdhip64.so")
         rt.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
         torch.cuda.synchronize(self.device)

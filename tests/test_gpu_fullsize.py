@@ -97,10 +97,10 @@ def _fullsize(gpu_lib, cfg, mode, n_tokens_e2e):
             xq_o, xs_o = om.quantize_rows(ff.bf16_bits_to_f64(x_bits[perm[rows] // cfg.k]))
             rt = torch.from_numpy(rows).to(dev)
             assert np.array_equal(layer.xq[rt].cpu().numpy(), xq_o), f"xq rows of expert {e}"
-            assert np.array_equal(layer.xs[rt].cpu().numpy(), xs_o), f"xs rows of expert {e}"
+            assert np.array_equal(layer.xs[:, rt].cpu().numpy().T, xs_o), f"xs rows of expert {e}"
             We = {n: inp[n][e].cpu().numpy() for n in ("W1q", "W3q", "W2q", "s1", "s3", "s2")}
             y_o, hq_o, hs_o = om.expert_ffn_rows(xq_o, xs_o, We["W1q"], We["s1"], We["W3q"], We["s3"], We["W2q"], We["s2"])
-            hq_g, hs_g = hq_all[rt].cpu().numpy(), hs_all[rt].cpu().numpy()
+            hq_g, hs_g = hq_all[rt].cpu().numpy(), np.ascontiguousarray(hs_all[:, rt].cpu().numpy().T)
             mism = float((hq_g != hq_o).mean())
             y_g = layer.y_perm[rt].cpu().numpy()
             rel = _rel_l2(y_g, y_o)

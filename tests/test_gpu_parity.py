@@ -105,12 +105,12 @@ def _run_and_check_layer(gpu_lib, cfg: MoEConfig, mode: str, seed=None):
         layer.quantize(dv["x"])
         xq_o, xs_o = om.gather_quantize(h["x"], perm, cfg.k)
         assert np.array_equal(layer.xq.cpu().numpy()[:cfg.N], xq_o)
-        assert np.array_equal(layer.xs.cpu().numpy()[:cfg.N], xs_o)
+        assert np.array_equal(layer.xs.cpu().numpy().T[:cfg.N], xs_o)      # device layout is [d/128, N]
 
         layer.expert_ffn(dv)
         y_o, hq_o, hs_o = om.expert_ffn(xq_o, xs_o, offsets, h["W1q"], h["W3q"], h["W2q"], h["s1"], h["s3"], h["s2"])
         hq_g, hs_g = layer.hidden()
-        hq_g, hs_g = hq_g.cpu().numpy()[:cfg.N], hs_g.cpu().numpy()[:cfg.N]
+        hq_g, hs_g = hq_g.cpu().numpy()[:cfg.N], np.ascontiguousarray(hs_g.cpu().numpy().T[:cfg.N])
         code_mismatch = float((hq_g != hq_o).mean())
         scale_rel = float(np.abs(hs_g - hs_o).max() / np.abs(hs_o).max())
         print(f"[{cfg.name}/{mode}] hq code mismatch fraction {code_mismatch:.2e}, hs max rel diff {scale_rel:.2e}")
@@ -234,11 +234,11 @@ def test_quantize_plain_and_edge_values(gpu_lib):
     layer = gpu_lib.MoELayer(1, 128, 1, 1, 128)
     try:
         q = torch.empty((257, 512), dtype=torch.uint8, device="cuda")
-        s = torch.empty((257, 4), dtype=torch.float32, device="cuda")
+        s = torch.empty((4, 257), dtype=torch.float32, device="cuda")          # group-major scale planes
         gpu_lib.moe_quantize_fp8(layer.ctx, xb.cuda(), 257, 512, 128, None, 1, q, s)
         torch.cuda.synchronize()
         q_o, s_o = om.quantize_rows(ff.bf16_bits_to_f64(_bits(xb)))
-        assert np.array_equal(s.cpu().numpy(), s_o)
+        assert np.array_equal(s.cpu().numpy().T, s_o)
         assert np.array_equal(q.cpu().numpy(), q_o)
         # rows_in = 0 is legal and touches nothing
         gpu_lib.moe_quantize_fp8(layer.ctx, xb.cuda(), 0, 512, 128, None, 1, q, s)
@@ -288,7 +288,7 @@ def test_zeroed_expert_and_integer_exactness(gpu_lib):
         t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
         layer.route_replay(None, t(idx), t(w))
         layer.xq.copy_(t(xq))
-        layer.xs.copy_(t(xs))
+        layer.xs.copy_(t(xs.T))
         layer.expert_ffn(dict(W1q=t(W1q), W3q=t(W3q), W2q=t(W2q), s1=t(s1), s3=t(s3), s2=t(s2)))
         torch.cuda.synchronize()
         y_o, hq_o, hs_o = om.expert_ffn(xq, xs, offsets, W1q, W3q, W2q, s1, s3, s2)
