@@ -20,6 +20,7 @@ namespace {
 
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int RT = 128;          // tokens per block
 constexpr int RKC = 64;          // hidden columns per staged activation chunk (128 bytes per row)
@@ -70,7 +71,7 @@ __global__ __launch_bounds__(256) void split_router_weights(const float* __restr
 
 // NS: 32-expert sub-tiles per wave (E_pad = 128*NS)
 template <int NS>
-__global__ __launch_bounds__(256, 2) void route_mfma_kernel(const uint16_t* __restrict__ x,
+__global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __restrict__ x,
                                                             const uint16_t* __restrict__ planes,
                                                             const float* __restrict__ bias, int T, int d, int E,
                                                             int k, int32_t* __restrict__ topk_idx,
@@ -85,22 +86,32 @@ __global__ __launch_bounds__(256, 2) void route_mfma_kernel(const uint16_t* __re
     const int t0 = blockIdx.x * RT;
     const int nk = d / 16, nchunks = d / RKC;
 
-    // activation staging: thread owns 16-byte chunk (row, c) for 4 rows
-    const int xc = tid & 7, xr = tid >> 3;
-    const uint16_t* xsrc[4];
-    uint32_t xdst[4];
+    // activation staging by direct-to-LDS copies: wave w, copy j brings rows (4w+j)*8 .. +7 of the chunk;
+    // lane i -> row i/8, LDS chunk slot i%8, which receives global 16-byte chunk
+    // slot ^ (row & 7) ^ ((row >> 3) & 1) (the operand reads then touch all 64 LDS banks evenly)
+    uint32_t xoff[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = xr + 32 * i;
+    for (int j = 0; j < 4; ++j) {
+        const int row = (wave * 4 + j) * 8 + (lane >> 3);
         const int t = min(t0 + row, T - 1);
-        xsrc[i] = x + (size_t)t * d + xc * 8;
-        xdst[i] = row * 128 + ((xc ^ (row & 7)) << 4);
+        xoff[j] = (uint32_t)t * (uint32_t)d * 2u + ((((lane & 7) ^ (row & 7) ^ ((row >> 3) & 1))) << 4);
     }
-    const uint4* wsrc[NS];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
+    auto issue_x = [&](int kc) {
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(x) + (size_t)kc * (RKC * 2);
+        const uint32_t dst = lds0 + (kc & 1) * RT * 128 + wave * 4 * 1024;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :: "s"(dst + j * 1024), "v"(xoff[j]), "s"(src) : "memory");
+    };
+    const v4i* wsrc[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-        wsrc[s] = reinterpret_cast<const uint4*>(planes) + ((size_t)(wave * NS + s) * nk * 3) * 64 + lane;
+        wsrc[s] = reinterpret_cast<const v4i*>(planes) + ((size_t)(wave * NS + s) * nk * 3) * 64 + lane;
 
+    // accumulators live in the accumulation registers for the whole K loop; the matrix instructions are
+    // volatile asm with a memory clobber, so they and the loads around them stay in source order
     v16f acc[NS][4];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
@@ -109,32 +120,58 @@ __global__ __launch_bounds__(256, 2) void route_mfma_kernel(const uint16_t* __re
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[s][ts][r] = 0.f;
 
-    uint4 xreg[4];
+    // Weight operands run three K steps ahead of the matrix cores in a ring of four register sets
+    // (a K step is 16 columns; a staged activation chunk holds four of them, so the ring slot of a
+    // step is its position inside the chunk): an L2 round trip is hidden behind ~70 MFMAs.
+    v4i a[4][NS][3];
+    auto load_a = [&](int slot, int kk) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) xreg[i] = *reinterpret_cast<const uint4*>(xsrc[i]);
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int p = 0; p < 3; ++p) a[slot][s][p] = wsrc[s][((size_t)kk * 3 + p) * 64];
+    };
+    issue_x(0);
+    load_a(0, 0);
+    load_a(1, 1);
+    load_a(2, 2);
 
     for (int kc = 0; kc < nchunks; ++kc) {
-        uint8_t* stage = smem + (kc & 1) * RT * 128;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) *reinterpret_cast<uint4*>(stage + xdst[i]) = xreg[i];
-        __syncthreads();
-        if (kc + 1 < nchunks) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) xreg[i] = *reinterpret_cast<const uint4*>(xsrc[i] + (size_t)(kc + 1) * RKC);
-        }
+        // chunk kc must have landed.  Vector-memory operations complete in issue order: after the copies
+        // of chunk kc this wave has issued exactly four K steps of weight loads (3*NS each), except
+        // before the first chunk.
+        if (kc == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        else if (NS == 2) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        __syncthreads();                                       // landed for everybody; chunk kc-1 fully consumed
+        if (kc + 1 < nchunks) issue_x(kc + 1);
+        const uint8_t* stage = smem + (kc & 1) * RT * 128;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const int kk = kc * 4 + ks;
-            uint4 a[NS][3];
-#pragma unroll
-            for (int s = 0; s < NS; ++s)
-#pragma unroll
-                for (int p = 0; p < 3; ++p) a[s][p] = wsrc[s][((size_t)kk * 3 + p) * 64];
-            uint4 b[4];
+            if (kk + 3 < nk) load_a((ks + 3) & 3, kk + 3);
+            v4i b[4];
 #pragma unroll
             for (int ts = 0; ts < 4; ++ts) {
                 const int row = ts * 32 + l32;
-                b[ts] = *reinterpret_cast<const uint4*>(stage + row * 128 + (((ks * 2 + half) ^ (row & 7)) << 4));
+                b[ts] = *reinterpret_cast<const v4i*>(stage + row * 128 + (((ks * 2 + half) ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
+            }
+            // The weight operands of this K step were requested three steps ago; vector-memory operations
+            // complete in issue order, so "at most as many outstanding as were issued since" means they
+            // have arrived.  (Written out by hand: the steady-state loop gets no automatic wait for
+            // values loaded in an earlier iteration and consumed by asm.)
+            // Three groups of 3*NS loads have been issued since, except in the last chunk, whose step ks
+            // is followed by 3 - ks groups only.
+            if (kc + 1 < nchunks || ks == 0) {
+                if (NS == 2) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
+            } else if (ks == 1) {
+                if (NS == 2) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+            } else if (ks == 2) {
+                if (NS == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+                else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+            } else {
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
 #pragma unroll
             for (int s = 0; s < NS; ++s)
@@ -142,10 +179,12 @@ __global__ __launch_bounds__(256, 2) void route_mfma_kernel(const uint16_t* __re
                 for (int p = 0; p < 3; ++p)
 #pragma unroll
                     for (int ts = 0; ts < 4; ++ts)
-                        acc[s][ts] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(v8bf, a[s][p]), __builtin_bit_cast(v8bf, b[ts]), acc[s][ts], 0, 0, 0);
+                        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
+                                     : "+a"(acc[s][ts]) : "v"(a[ks][s][p]), "v"(b[ts]) : "memory");
         }
     }
+    // the last matrix instructions must have left the pipe before the accumulators are read
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __syncthreads();                                           // all reads of the activation stages are done
 
     // ---- per-wave top-k.  Lane (l32, half) holds, for token ts*32+l32, the logits of experts
