@@ -212,11 +212,18 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
 #pragma unroll
         for (int j = 0; j < 4; ++j) dma16(dst + j * 8 * KB, w_off[j], src);
     };
+    // 8-row activation copies that lie wholly beyond the expert's last row are not issued at all
+    // (a ragged last tile then moves only the rows it has); wave-uniform
+    const int x_copies = __builtin_amdgcn_readfirstlane(max(0, min(4, (row_end - wk.row0 - wave * 32 + 7) / 8)));
     auto issue_x = [&](int kb, int xslot) {
         const uint8_t* src = x_base + (size_t)kb * KB;
         const uint32_t dst = lds_rows + X_RING + xslot * X_TILE;
+        // the skip is a scalar branch inside the asm: the compiler's control flow stays a straight line
 #pragma unroll
-        for (int j = 0; j < 4; ++j) dma16(dst + j * 8 * KB, x_off[j], src);
+        for (int j = 0; j < 4; ++j)
+            asm volatile("s_cmp_gt_i32 %3, %4\n\ts_cbranch_scc0 .Lskipx%=\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\t"
+                         "global_load_lds_dwordx4 %1, %2\n.Lskipx%=:"
+                         :: "s"(dst + j * 8 * KB), "v"(x_off[j]), "s"(src), "s"(x_copies), "n"(j) : "memory", "scc");
     };
 
     // ---- weight scales of this wave's rows (wave-uniform -> scalar loads)
