@@ -1,9 +1,9 @@
 // Stable counting sort of the T*k (token, slot) assignments by expert id.
 //
 // Three atomics-free kernels:
-//   1. chunk_hist_rank: each block stages PERM_CHUNK ids in LDS; thread e walks the
-//      chunk in order and numbers the entries that name expert e, which yields the
-//      chunk's histogram and every entry's rank among earlier equal ids of the chunk.
+//   1. chunk_hist_rank: each block ranks PERM_CHUNK ids with wave ballots and per-wave
+//      running counts in LDS, which yields the chunk's histogram and every entry's rank
+//      among earlier equal ids of the chunk.
 //   2. scan_chunks: one block turns the per-chunk histograms into exclusive prefix
 //      sums over chunks (per expert) and the expert totals into offsets[0..E].
 //   3. scatter: position = offsets[e] + prefix[chunk][e] + rank; writes perm/inv_perm.
@@ -13,39 +13,64 @@
 namespace moe355 {
 namespace {
 
+// Each of the four waves ranks a quarter of the chunk, 64 entries at a time: eight ballots (one per
+// bit of the expert id) give every lane the set of lanes that hold the same id, its rank among them is
+// a population count of the lower lanes, and the lowest lane of each set advances that expert's running
+// count, kept per wave in LDS (read by the whole set, then written by one lane: LDS operations of a wave
+// execute in order).  A second pass turns the per-wave counts into the chunk histogram and the per-wave
+// bases.  Ids outside [0,E) are ranked among themselves; that rank is never used.
 __global__ __launch_bounds__(256) void chunk_hist_rank(const int32_t* __restrict__ ids, int N, int E,
                                                        int32_t* __restrict__ chunk_counts,
                                                        int32_t* __restrict__ rank_out,
                                                        int32_t* __restrict__ ids_copy) {
-    __shared__ int32_t s_id[PERM_CHUNK];
-    __shared__ uint16_t s_rank[PERM_CHUNK];
-    const int tid = threadIdx.x;
+    constexpr int PER_WAVE = PERM_CHUNK / 4;          // 512 entries, 8 steps of 64
+    __shared__ int32_t s_cnt[4][MAX_E];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int base = blockIdx.x * PERM_CHUNK;
-    const int len = min(PERM_CHUNK, N - base);
-    for (int i = tid; i < PERM_CHUNK; i += 256) {
+    for (int i = tid; i < 4 * MAX_E; i += 256) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+    int32_t my_id[PER_WAVE / 64], my_rank[PER_WAVE / 64];
+    const uint64_t lower = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int st = 0; st < PER_WAVE / 64; ++st) {
+        const int i = base + wave * PER_WAVE + st * 64 + lane;
         int32_t v = -1;
-        if (i < len) {
-            v = ids[base + i];
-            if (ids_copy) ids_copy[base + i] = v;
+        if (i < N) {
+            v = ids[i];
+            if (ids_copy) ids_copy[i] = v;
         }
-        s_id[i] = v;
-        s_rank[i] = 0;
+        const bool valid = v >= 0 && v < E;           // entries past the end and bad ids form a class of their own
+        my_id[st] = v;
+        const int key = v & (MAX_E - 1);
+        uint64_t same = __ballot(valid);              // lanes past the end never match a valid lane
+        if (!valid) same = ~same;
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const uint64_t bal = __ballot((key >> bit) & 1);
+            same &= ((key >> bit) & 1) ? bal : ~bal;
+        }
+        const int before = s_cnt[wave][key];
+        my_rank[st] = before + __popcll(same & lower);
+        if (valid && (same & lower) == 0ull) s_cnt[wave][key] = before + __popcll(same);
     }
     __syncthreads();
-    if (tid < E) {
-        int cnt = 0;
-        const int len4 = (len + 3) & ~3;              // padded entries hold -1 and never match
-        for (int i = 0; i < len4; i += 4) {
-            const int4 v = *reinterpret_cast<const int4*>(&s_id[i]);
-            if (v.x == tid) s_rank[i] = (uint16_t)cnt++;
-            if (v.y == tid) s_rank[i + 1] = (uint16_t)cnt++;
-            if (v.z == tid) s_rank[i + 2] = (uint16_t)cnt++;
-            if (v.w == tid) s_rank[i + 3] = (uint16_t)cnt++;
+    // thread e: per-wave bases (exclusive over waves) and the chunk total of expert e
+    if (tid < MAX_E) {
+        int run = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int c = s_cnt[w][tid];
+            s_cnt[w][tid] = run;
+            run += c;
         }
-        chunk_counts[(size_t)blockIdx.x * E + tid] = cnt;
+        if (tid < E) chunk_counts[(size_t)blockIdx.x * E + tid] = run;
     }
     __syncthreads();
-    for (int i = tid; i < len; i += 256) rank_out[base + i] = s_rank[i];
+#pragma unroll
+    for (int st = 0; st < PER_WAVE / 64; ++st) {
+        const int i = base + wave * PER_WAVE + st * 64 + lane;
+        if (i < N) rank_out[i] = my_rank[st] + s_cnt[wave][my_id[st] & (MAX_E - 1)];
+    }
 }
 
 __global__ __launch_bounds__(256) void scan_chunks(int32_t* __restrict__ chunk_counts, int n_chunks,
