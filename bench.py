@@ -22,6 +22,21 @@ if ROOT not in sys.path:
 
 FP8_PEAK_TFLOPS = 5000.0   # MI355X dense FP8 MFMA peak
 HBM_PEAK_GBS = 8000.0      # MI355X HBM3E
+CALIB_BYTES = 1 << 30      # size of the plain device copy that calibrates the HBM byte counters
+
+
+def _measured_traffic(config_index):
+    """HBM bytes per launch of the gate/up GEMM, as recorded in the committed counter summary
+    (profiles/ffn_gemm_cfg<i>_hbm_traffic.txt, line 'gemm1_hbm_bytes_per_launch: <number>'); None if absent."""
+    path = os.path.join(ROOT, "profiles", f"ffn_gemm_cfg{config_index}_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("gemm1_hbm_bytes_per_launch:"):
+                    return float(line.split(":", 1)[1].strip())
+    except OSError:
+        pass
+    return None
 
 
 def _cpu_baseline(cfg, inp_small):
@@ -73,6 +88,12 @@ def main() -> int:
     torch.cuda.synchronize()
     layer = moe.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, device=dev)
     x, W_r, bias = inp["x"], inp["W_r"], inp.get("sel_bias")
+    # a plain copy of known size: under `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its counters give the
+    # factor that turns the same counters of the GEMM kernels into bytes
+    calib = torch.empty(CALIB_BYTES, dtype=torch.uint8, device=dev)
+    calib_dst = torch.empty_like(calib)
+    calib_dst.copy_(calib)
+    del calib, calib_dst
     K, W = args.steps, args.warmup
 
     def step_routed():
@@ -141,13 +162,14 @@ def main() -> int:
     c_bytes = 4.0 * N * d + 8.0 * N + 2.0 * T * d
     roof = {"bound": "mfma", "kernel": "ffn_gemm<gate/up> (GEMM1 + SwiGLU + h re-quantisation)",
             "achieved": gemm1_flop / (g1 * 1e-3) / 1e12, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": gemm1_flop / (g1 * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, "traffic": None,
+            "frac": gemm1_flop / (g1 * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, "traffic": _measured_traffic(args.config),
+            "algorithmic_bytes": 2.0 * cfg.E * d * F + N * d + N * F,
             "avg_launch_ms": g1, "flop_per_launch": gemm1_flop}
     out = {
         "metric": "MoE-layer fwd FP8 TFLOP/s (% MFMA peak) + tokens/s, routed vs replay",
         "value": flop / (ms_head * 1e-3) / 1e12, "unit": "TFLOP/s",
         "n_gpus": 1, "steps": K, "warmup": W, "ms_per_step": ms_head, "higher_is_better": True,
-        "scaling": "weak", "vs_baseline": None, "dtype": "fp8_e4m3 (fp32 accumulate)", "data": "synthetic",
+        "scaling": "weak", "vs_baseline": None, "dtype": "fp8", "data": "synthetic",
         "config": {"workload": f"configs[{args.config}] {cfg.name}: T={T} d={d} E={cfg.E} k={k} F={F}, mode={head_mode}",
                    "T": T, "d": d, "E": cfg.E, "k": k, "F": F, "mode": head_mode},
         "pct_mfma_peak_whole_step": 100.0 * flop / (ms_head * 1e-3) / 1e12 / FP8_PEAK_TFLOPS,

@@ -1,10 +1,10 @@
 // Grouped block-scaled FP8 SwiGLU expert FFN on the CDNA4 matrix cores.
 //
-// Work unit: a tile of TOK_TILE (256) expert-sorted rows x 256 staged weight rows.  A small
-// kernel turns offsets[] into the list of work units (expert, first row, feature tile), so
-// ragged experts need no host round trip, and orders it so that units sharing a weight tile
-// are adjacent; blocks map onto the list so that each XCD (blockIdx % 8) walks a contiguous
-// range and its L2 sees every weight tile once.
+// Work unit: a tile of up to TOK_TILE (256) expert-sorted rows x 256 staged weight rows.  A
+// small kernel turns offsets[] into the list of work units (expert, first row, feature tile,
+// rows), so ragged experts need no host round trip, and orders it so that units sharing a
+// weight tile are adjacent; blocks map onto the list so that each XCD (blockIdx % 8) walks a
+// contiguous range and its L2 sees every weight tile once.
 //
 // Main loop, one iteration per 128-wide K block (= one scale block):
 //   * both operand tiles are copied global -> LDS by direct-to-LDS loads (no staging
@@ -44,59 +44,48 @@ constexpr int X_RING = NW_BUF * W_TILE;            // byte offset of the activat
 constexpr int NTHREADS = 512;
 constexpr int NXCD = 8;
 
-struct Work { int32_t expert; int32_t row0; int32_t ft; };
+struct Work { int32_t expert; int32_t row0; int32_t ft; int32_t nrows; };
 
 // ------------------------------------------------------------------ work list
-// One thread per expert.  Full 256-row tiles of all experts come first, ordered (expert,
-// feature tile, row tile); the ragged last tiles follow, ordered (expert, feature tile).
-// Units that share a weight tile or an activation tile are thus neighbours AND do the same
-// amount of work, so the blocks that run them side by side on one XCD advance in step and
-// hit each other's lines in that XCD's L2 (a few K steps of skew already exceed what the L2
-// retains, and the shared tile is then fetched again from HBM).
+// One thread per expert.  An expert with c rows gets ceil(c/256) row tiles of (nearly) equal
+// height, ordered (expert, feature tile, row tile).  Units that share a weight tile are thus
+// neighbours AND do the same amount of work, so the blocks that run them side by side on one XCD
+// advance in step and hit each other's lines in that XCD's L2 (a few K steps of skew already exceed
+// what the L2 retains, and the shared tile is then fetched again from HBM); no expert leaves a short
+// last tile behind that would have to stream the whole weight tile for a handful of rows.
 __global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ offsets, int E, int n_ft,
                                                   Work* __restrict__ work, int32_t* __restrict__ n_work) {
-    __shared__ int32_t s_full[MAX_E];
-    __shared__ int32_t s_tail[MAX_E];
+    __shared__ int32_t s_tiles[MAX_E];
     const int tid = threadIdx.x;
     int start = 0, cnt = 0;
     if (tid < E) {
         start = offsets[tid];
         cnt = offsets[tid + 1] - start;
     }
-    const int full = cnt / TOK_TILE;
-    const int tail = (cnt % TOK_TILE) ? 1 : 0;
-    s_full[tid] = full;
-    s_tail[tid] = tail;
+    const int nt = (cnt + TOK_TILE - 1) / TOK_TILE;
+    s_tiles[tid] = nt;
     __syncthreads();
     for (int off = 1; off < MAX_E; off <<= 1) {
-        const int a = (tid >= off) ? s_full[tid - off] : 0;
-        const int b = (tid >= off) ? s_tail[tid - off] : 0;
+        const int a = (tid >= off) ? s_tiles[tid - off] : 0;
         __syncthreads();
-        s_full[tid] += a;
-        s_tail[tid] += b;
+        s_tiles[tid] += a;
         __syncthreads();
     }
-    const int all_full = s_full[MAX_E - 1];
-    const int base_full = (s_full[tid] - full) * n_ft;
-    for (int f = 0; f < n_ft; ++f)
-        for (int i = 0; i < full; ++i) {
-            Work w;
-            w.expert = tid;
-            w.row0 = start + i * TOK_TILE;
-            w.ft = f;
-            work[base_full + f * full + i] = w;
-        }
-    if (tail) {
-        const int base_tail = (all_full + s_tail[tid] - 1) * n_ft;
-        for (int f = 0; f < n_ft; ++f) {
-            Work w;
-            w.expert = tid;
-            w.row0 = start + full * TOK_TILE;
-            w.ft = f;
-            work[base_tail + f] = w;
-        }
+    if (nt > 0) {
+        const int base = (s_tiles[tid] - nt) * n_ft;
+        for (int f = 0; f < n_ft; ++f)
+            for (int i = 0; i < nt; ++i) {
+                // tile i covers rows [i*cnt/nt, (i+1)*cnt/nt): between 1 and 256 rows each
+                const int lo = (int)((int64_t)i * cnt / nt), hi = (int)((int64_t)(i + 1) * cnt / nt);
+                Work w;
+                w.expert = tid;
+                w.row0 = start + lo;
+                w.ft = f;
+                w.nrows = hi - lo;
+                work[base + f * nt + i] = w;
+            }
     }
-    if (tid == MAX_E - 1) *n_work = (all_full + s_tail[tid]) * n_ft;
+    if (tid == MAX_E - 1) *n_work = s_tiles[tid] * n_ft;
 }
 
 // ------------------------------------------------------------------ helpers
@@ -170,7 +159,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     if (slot >= chunk || wi >= total) return;
     const Work wk = work[wi];
     const int e = wk.expert;
-    const int row_end = offsets[e + 1];
+    const int row_end = wk.row0 + wk.nrows;                    // this tile's rows only
     const int f0 = wk.ft * FT;
 
     const int tid = threadIdx.x;
