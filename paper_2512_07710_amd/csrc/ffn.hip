@@ -47,45 +47,48 @@ constexpr int NXCD = 8;
 struct Work { int32_t expert; int32_t row0; int32_t ft; int32_t nrows; };
 
 // ------------------------------------------------------------------ work list
-// One thread per expert.  An expert with c rows gets ceil(c/256) row tiles of (nearly) equal
-// height, ordered (expert, feature tile, row tile).  Units that share a weight tile are thus
-// neighbours AND do the same amount of work, so the blocks that run them side by side on one XCD
-// advance in step and hit each other's lines in that XCD's L2 (a few K steps of skew already exceed
-// what the L2 retains, and the shared tile is then fetched again from HBM); no expert leaves a short
-// last tile behind that would have to stream the whole weight tile for a handful of rows.
-__global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ offsets, int E, int n_ft,
-                                                  Work* __restrict__ work, int32_t* __restrict__ n_work) {
+// An expert with c rows gets ceil(c/256) row tiles of (nearly) equal height, ordered (expert,
+// feature tile, row tile).  Units that share a weight tile are thus neighbours AND do the same
+// amount of work, so the blocks that run them side by side on one XCD advance in step and hit each
+// other's lines in that XCD's L2 (a few K steps of skew already exceed what the L2 retains, and the
+// shared tile is then fetched again from HBM); no expert leaves a short last tile behind that would
+// have to stream the whole weight tile for a handful of rows.
+// Block (e, l) writes the units of expert e into list l (0: gate/up, n_ft0 feature tiles; 1: down,
+// n_ft1 feature tiles); every block recomputes the tile counts of all experts for its base index.
+__global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ offsets, int E, int n_ft0, int n_ft1,
+                                                  Work* __restrict__ work0, Work* __restrict__ work1,
+                                                  int32_t* __restrict__ n_work) {
     __shared__ int32_t s_tiles[MAX_E];
     const int tid = threadIdx.x;
-    int start = 0, cnt = 0;
-    if (tid < E) {
-        start = offsets[tid];
-        cnt = offsets[tid + 1] - start;
-    }
-    const int nt = (cnt + TOK_TILE - 1) / TOK_TILE;
-    s_tiles[tid] = nt;
+    const int e = blockIdx.x;
+    const int n_ft = blockIdx.y == 0 ? n_ft0 : n_ft1;
+    Work* const work = blockIdx.y == 0 ? work0 : work1;
+    int nt_t = 0;
+    if (tid < E) nt_t = (offsets[tid + 1] - offsets[tid] + TOK_TILE - 1) / TOK_TILE;
+    s_tiles[tid] = nt_t;
     __syncthreads();
-    for (int off = 1; off < MAX_E; off <<= 1) {
+    for (int off = 1; off < MAX_E; off <<= 1) {            // inclusive scan
         const int a = (tid >= off) ? s_tiles[tid - off] : 0;
         __syncthreads();
         s_tiles[tid] += a;
         __syncthreads();
     }
-    if (nt > 0) {
-        const int base = (s_tiles[tid] - nt) * n_ft;
-        for (int f = 0; f < n_ft; ++f)
-            for (int i = 0; i < nt; ++i) {
-                // tile i covers rows [i*cnt/nt, (i+1)*cnt/nt): between 1 and 256 rows each
-                const int lo = (int)((int64_t)i * cnt / nt), hi = (int)((int64_t)(i + 1) * cnt / nt);
-                Work w;
-                w.expert = tid;
-                w.row0 = start + lo;
-                w.ft = f;
-                w.nrows = hi - lo;
-                work[base + f * nt + i] = w;
-            }
+    if (e == 0 && tid == 0) n_work[blockIdx.y] = s_tiles[MAX_E - 1] * n_ft;
+    const int start = offsets[e], cnt = offsets[e + 1] - start;
+    const int nt = (cnt + TOK_TILE - 1) / TOK_TILE;
+    if (nt == 0) return;
+    const int base = (s_tiles[e] - nt) * n_ft;
+    for (int idx = tid; idx < nt * n_ft; idx += 256) {
+        const int f = idx / nt, i = idx - f * nt;
+        // tile i covers rows [i*cnt/nt, (i+1)*cnt/nt): between 1 and 256 rows each
+        const int lo = (int)((int64_t)i * cnt / nt), hi = (int)((int64_t)(i + 1) * cnt / nt);
+        Work w;
+        w.expert = e;
+        w.row0 = start + lo;
+        w.ft = f;
+        w.nrows = hi - lo;
+        work[base + idx] = w;
     }
-    if (tid == MAX_E - 1) *n_work = s_tiles[tid] * n_ft;
 }
 
 // ------------------------------------------------------------------ helpers
@@ -504,8 +507,8 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, con
     const int nft2 = (D.d + 255) / 256;
     Work* work2 = work + (size_t)c->max_tiles * nft1;          // the down projection's list
     int32_t* n_work2 = c->n_tiles + 1;
-    hipLaunchKernelGGL(build_work, dim3(1), dim3(256), 0, c->stream, offsets, D.E, nft1, work, c->n_tiles);
-    hipLaunchKernelGGL(build_work, dim3(1), dim3(256), 0, c->stream, offsets, D.E, nft2, work2, n_work2);
+    hipLaunchKernelGGL(build_work, dim3(D.E, 2), dim3(256), 0, c->stream, offsets, D.E, nft1, nft2, work, work2,
+                       c->n_tiles);
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     const int grid1 = ((c->max_tiles * nft1 + NXCD - 1) / NXCD) * NXCD;
     hipLaunchKernelGGL((ffn_gemm<true>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, (int)((int64_t)D.T * D.k), offsets,
