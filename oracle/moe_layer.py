@@ -11,7 +11,11 @@ standard definitions below are the reading taken):
            ties to the lower index, slots in descending score order; gate
            weights = softmax over the k selected unbiased logits.
   replay   the logged expert ids and gate weights are used verbatim
-           (router decisions recorded at rollout are reused by the trainer).
+           (router decisions recorded at rollout are reused by the trainer);
+           ids-only form: the ids are reused, the weights are the softmax of
+           this engine's own logits over the logged ids.
+  weights  block-wise quantisation of a weight matrix: one scale per 128x128
+           block, same scale and rounding rule as for activations.
   permute  stable counting sort of the T*k (token, slot) assignments by expert.
   quantise each row, per 128 contiguous elements: s = amax/448 (1 if amax=0),
            code = e4m3(x/s); s and x/s are rounded to fp32 before use.
@@ -64,6 +68,17 @@ def route_replay(logged_idx, logged_w):
     return np.array(logged_idx, dtype=np.int32, copy=True), np.array(logged_w, dtype=np.float32, copy=True)
 
 
+def route_replay_ids(x_bits, W_r, logged_idx):
+    """Ids-only Router Replay (section 2.4.4 read literally: the router DECISIONS are reused).
+
+    The logged expert ids are taken verbatim; the gate weights are recomputed from this engine's own
+    logits, w[t,j] = softmax over logit[t, logged_idx[t,:]].  Returns (idx i32, w f32, logits f64).
+    """
+    logits = router_logits(x_bits, W_r)
+    idx = np.array(logged_idx, dtype=np.int32, copy=True)
+    return idx, gate_weights(logits, idx), logits
+
+
 def permute(topk_idx: np.ndarray, E: int):
     """Stable counting sort of flat assignments i = t*k+j by expert id.
 
@@ -106,6 +121,29 @@ def quantize_rows(v: np.ndarray):
     r = (vg / s.astype(np.float64)[:, :, None]).astype(np.float32)
     codes = e4m3_encode(r.astype(np.float64)).reshape(R, C)
     return codes, s
+
+
+def quantize_blocks(w: np.ndarray):
+    """Block-wise weight quantisation (section 3.1.2: weights are quantised block-wise when the trainer
+    pushes them to the rollout engine).
+
+    w [R,C] float64 holding fp32-representable values, R and C multiples of 128.  One fp32 scale per
+    128x128 block: s = fp32(amax/448) (1 if the block is all zero), code = e4m3(fp32(w/s)).
+    Returns codes u8 [R,C] and scales f32 [R/128, C/128].
+    """
+    R, C = w.shape
+    assert R % G == 0 and C % G == 0
+    codes = np.zeros((R, C), dtype=np.uint8)
+    scales = np.ones((R // G, C // G), dtype=np.float32)
+    for bi in range(R // G):
+        for bj in range(C // G):
+            blk = w[bi * G:(bi + 1) * G, bj * G:(bj + 1) * G]
+            amax = np.abs(blk).max()
+            s = np.float32(1.0) if amax == 0 else np.float32(amax / E4M3_MAX)
+            r = (blk / np.float64(s)).astype(np.float32)
+            codes[bi * G:(bi + 1) * G, bj * G:(bj + 1) * G] = e4m3_encode(r.astype(np.float64))
+            scales[bi, bj] = s
+    return codes, scales
 
 
 def gather_quantize(x_bits: np.ndarray, perm: np.ndarray, k: int):

@@ -354,3 +354,73 @@ def test_combine_is_weighted_gather():
         ref = sum(float(w[t, j]) * y_perm[inv[t * k + j]] for j in range(k))
         assert np.allclose(y[t], ref, rtol=1e-14)
     assert np.array_equal(bits, ff.f64_to_bf16_bits(y))
+
+
+# --------------------------------------------------------------------------- ids-only replay
+def test_replay_ids_closed_forms():
+    """Weights recomputed over the logged ids: brute force, permutation equivariance, k = E, own ids."""
+    from scipy.special import softmax
+    rng = np.random.default_rng(5)
+    T, d, E, k = 12, 128, 8, 3
+    x = ff.f64_to_bf16_bits(rng.standard_normal((T, d)))
+    W_r = rng.standard_normal((E, d)).astype(np.float32) / np.sqrt(d)
+    ids = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    idx, w, logits = om.route_replay_ids(x, W_r, ids)
+    assert np.array_equal(idx, ids)
+    xf = ff.bf16_bits_to_f64(x)
+    for t in range(T):                                   # token by token, expert by expert
+        lg = np.array([sum(float(xf[t, c]) * float(W_r[e, c]) for c in range(d)) for e in ids[t]])
+        p = np.exp(lg - lg.max())
+        assert np.allclose(w[t], p / p.sum(), rtol=1e-6, atol=1e-7)
+    assert np.allclose(w.sum(axis=1), 1.0, atol=1e-6)
+    # reordering the logged slots reorders the weights and nothing else
+    order = np.array([2, 0, 1])
+    _, w2, _ = om.route_replay_ids(x, W_r, ids[:, order])
+    assert np.array_equal(w2, w[:, order])
+    # k = E: the plain softmax over all experts, in the logged order
+    all_ids = np.tile(np.arange(E, dtype=np.int32)[::-1], (T, 1))
+    _, w_all, lg_all = om.route_replay_ids(x, W_r, all_ids)
+    assert np.allclose(w_all, softmax(lg_all, axis=1)[:, ::-1], rtol=1e-6, atol=1e-7)
+    # logging the router's own choice reproduces the routed weights bit for bit
+    r_idx, r_w, _ = om.route(x, W_r, k)
+    _, w3, _ = om.route_replay_ids(x, W_r, r_idx)
+    assert np.array_equal(w3, r_w)
+    # the log decides the ids even where the router would choose otherwise
+    assert not np.array_equal(ids, r_idx)
+
+
+# --------------------------------------------------------------------------- block-wise weight quantisation
+def test_quantize_blocks_invariants_and_torch_recipe():
+    rng = np.random.default_rng(11)
+    w = rng.standard_normal((256, 384)) / 30.0
+    w[:128, 128:256] = 0.0                                # an all-zero block
+    w[128:, :128] = np.exp2(rng.integers(-6, 3, (128, 128)))   # powers of two: exact
+    w[130, 300] = 7.5                                      # an outlier that owns its block's scale
+    wb = ff.bf16_bits_to_f64(ff.f64_to_bf16_bits(w))       # the trainer's weights are bf16
+    q, s = om.quantize_blocks(wb)
+    assert q.shape == (256, 384) and s.shape == (2, 3) and s.dtype == np.float32
+    dec = ff.e4m3_decode(q)
+    for bi in range(2):
+        for bj in range(3):
+            blk = wb[bi * 128:(bi + 1) * 128, bj * 128:(bj + 1) * 128]
+            d_blk = dec[bi * 128:(bi + 1) * 128, bj * 128:(bj + 1) * 128]
+            if np.abs(blk).max() == 0:
+                assert s[bi, bj] == 1.0 and not q[bi * 128:(bi + 1) * 128, bj * 128:(bj + 1) * 128].any()
+                continue
+            assert np.abs(d_blk).max() == 448.0            # the block maximum lands on the largest code
+            assert s[bi, bj] == np.float32(np.abs(blk).max() / 448.0)
+            half_step = np.maximum(np.abs(d_blk) / 16.0, 2.0 ** -10)       # half an e4m3 step at that magnitude
+            assert np.all(np.abs(blk / np.float64(s[bi, bj]) - d_blk) <= half_step * (1 + 1e-6))
+    assert s[1, 2] == np.float32(7.5 / 448.0)
+    # powers of two divided by a power-of-two-times-7/4 scale: check against plain float32 arithmetic + torch's cast
+    wt = torch.from_numpy(wb.astype(np.float32))
+    st = torch.from_numpy(s)
+    rt = (wt.view(2, 128, 3, 128) / st[:, None, :, None]).reshape(256, 384)
+    q_t = rt.to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(q, q_t)
+    # a matrix whose 128-row blocks consist of identical rows: block scales = row-group scales
+    row = rng.standard_normal((1, 256))
+    wr = ff.bf16_bits_to_f64(ff.f64_to_bf16_bits(np.repeat(row, 128, axis=0)))
+    qb, sb = om.quantize_blocks(wr)
+    qr, sr = om.quantize_rows(wr)
+    assert np.array_equal(qb, qr) and np.array_equal(np.repeat(sb, 128, axis=0), sr)
