@@ -82,6 +82,17 @@ int moe_route_replay(moe_ctx* ctx, const uint16_t* x_bf16, const int32_t* logged
                      const float* logged_w, int32_t* topk_idx, float* topk_w,
                      int32_t* offsets, int32_t* perm, int32_t* inv_perm);
 
+/* Ids-only Router Replay (section 2.4.4 read literally: the router's DECISIONS are reused).  The logged
+ * expert ids are copied to topk_idx; the gate weights are recomputed from this engine's own logits,
+ * topk_w[t,j] = softmax over logit[t, logged_idx[t,0..k-1]] (same logits, same arithmetic as moe_route, so
+ * logging moe_route's own ids reproduces its weights bit for bit).  No selection bias takes part.  Then the
+ * permutation is built as in moe_route_replay.  Ids outside [0,E) never fault: their weight is computed
+ * from logit 0, their assignments are skipped and moe_check_ids reports them.
+ *   x_bf16 [T,d]; W_router [E,d] fp32; logged_idx [T,k] i32; outputs as moe_route. */
+int moe_route_replay_ids(moe_ctx* ctx, const uint16_t* x_bf16, const float* W_router,
+                         const int32_t* logged_idx, int32_t* topk_idx, float* topk_w,
+                         int32_t* offsets, int32_t* perm, int32_t* inv_perm);
+
 /* Synchronises the stream and returns MOE_EBADIDS if any routing call on this
  * context since the last check met an expert id outside [0,E), else MOE_OK. */
 int moe_check_ids(moe_ctx* ctx);
@@ -103,6 +114,25 @@ int moe_check_ids(moe_ctx* ctx);
 int moe_quantize_fp8(moe_ctx* ctx, const uint16_t* x_bf16, int64_t rows_in, int32_t cols,
                      int32_t block, const int32_t* dst_rows, int32_t fanout,
                      uint8_t* q, float* scales);
+
+/* Block-wise FP8 quantisation of a weight matrix (section 3.1.2: the weight-update path quantises
+ * the trainer's weights block-wise before handing them to the FP8 rollout engine).  One fp32 scale per
+ * 128x128 block: s = amax/448 (1.0 for an all-zero block), code = e4m3(w/s) with fp32 division, round
+ * to nearest even, saturating: the weight format moe_expert_ffn_fp8 and moe_linear_fp8 consume.
+ *   w_bf16 [rows, cols] row-major, rows and cols multiples of 128 (an [E,F,d] tensor is passed as
+ *   rows = E*F, cols = d); q [rows, cols] u8; scales [rows/128, cols/128] f32. */
+int moe_quantize_weights_fp8(moe_ctx* ctx, const uint16_t* w_bf16, int64_t rows, int32_t cols,
+                             uint8_t* q, float* scales);
+
+/* Dense block-scaled FP8 linear layer (section 3.1.2 applies FP8 to "Linear and MoE layers"):
+ *   y[p,n] = sum_kb xs[kb,p]*ws[n/128,kb] * sum_{c in block kb} xq[p,c]*Wq[n,c],  fp32 out.
+ * The grouped down-projection kernel with one group that owns every row.
+ *   xq [rows,K] u8 and xs [K/128][rows] f32 as written by moe_quantize_fp8 (dst_rows = NULL);
+ *   Wq [NOUT,K] u8; ws [NOUT/128, K/128] f32; y [rows,NOUT] f32.  K and NOUT multiples of 128.
+ * Uses the context's work-list storage: ceil(rows/256)*ceil(NOUT/256) must not exceed
+ * (T*k/256 + E) * (F/128 + ceil(d/256)) of the context's dims, else MOE_EINVAL. */
+int moe_linear_fp8(moe_ctx* ctx, const uint8_t* xq, const float* xs, int32_t rows, int32_t K,
+                   const uint8_t* Wq, const float* ws, int32_t NOUT, float* y);
 
 /* Grouped SwiGLU expert FFN on expert-sorted rows.  For expert e and rows
  * p in [offsets[e], offsets[e+1]):

@@ -17,9 +17,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 _lib: Optional[ctypes.CDLL] = None
 
-EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_check_ids",
-           "moe_quantize_fp8", "moe_expert_ffn_fp8", "moe_combine", "moe_debug_hidden", "moe_profile_enable",
-           "moe_profile_read", "moe_version")
+EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_route_replay_ids",
+           "moe_check_ids", "moe_quantize_fp8", "moe_quantize_weights_fp8", "moe_linear_fp8", "moe_expert_ffn_fp8",
+           "moe_combine", "moe_debug_hidden", "moe_profile_enable", "moe_profile_read", "moe_version")
 
 
 class MoEError(RuntimeError):
@@ -49,7 +49,10 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_version.restype = ctypes.c_char_p
     lib.moe_route.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.moe_route_replay.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
+    lib.moe_route_replay_ids.argtypes = [vp] * 9
     lib.moe_check_ids.argtypes = [vp]
+    lib.moe_quantize_weights_fp8.argtypes = [vp, vp, i64, i32, vp, vp]
+    lib.moe_linear_fp8.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
     lib.moe_quantize_fp8.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp]
     lib.moe_expert_ffn_fp8.argtypes = [vp] * 11
     lib.moe_combine.argtypes = [vp] * 5
@@ -115,6 +118,25 @@ def moe_route_replay(ctx, x, logged_idx, logged_w, topk_idx, topk_w, offsets, pe
 def moe_check_ids(ctx) -> int:
     """Returns the raw status (0 or MOE_EBADIDS) after synchronising the context's stream."""
     return load_library().moe_check_ids(ctx)
+
+
+def moe_route_replay_ids(ctx, x, W_router, logged_idx, topk_idx, topk_w, offsets, perm, inv_perm) -> None:
+    i32 = torch.int32
+    _check(load_library().moe_route_replay_ids(ctx, _ptr(x, torch.bfloat16), _ptr(W_router, torch.float32),
+                                               _ptr(logged_idx, i32), _ptr(topk_idx, i32),
+                                               _ptr(topk_w, torch.float32), _ptr(offsets, i32), _ptr(perm, i32),
+                                               _ptr(inv_perm, i32)), "moe_route_replay_ids")
+
+
+def moe_quantize_weights_fp8(ctx, w, rows, cols, q, scales) -> None:
+    _check(load_library().moe_quantize_weights_fp8(ctx, _ptr(w, torch.bfloat16), rows, cols, _ptr(q, torch.uint8),
+                                                   _ptr(scales, torch.float32)), "moe_quantize_weights_fp8")
+
+
+def moe_linear_fp8(ctx, xq, xs, rows, K, Wq, ws, NOUT, y) -> None:
+    u8, f32 = torch.uint8, torch.float32
+    _check(load_library().moe_linear_fp8(ctx, _ptr(xq, u8), _ptr(xs, f32), rows, K, _ptr(Wq, u8), _ptr(ws, f32),
+                                         NOUT, _ptr(y, f32)), "moe_linear_fp8")
 
 
 def moe_quantize_fp8(ctx, x, rows_in, cols, block, dst_rows, fanout, q, scales) -> None:

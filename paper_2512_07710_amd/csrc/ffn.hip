@@ -74,6 +74,7 @@ __global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ of
         __syncthreads();
     }
     if (e == 0 && tid == 0) n_work[blockIdx.y] = s_tiles[MAX_E - 1] * n_ft;
+    if (e >= E) return;
     const int start = offsets[e], cnt = offsets[e + 1] - start;
     const int nt = (cnt + TOK_TILE - 1) / TOK_TILE;
     if (nt == 0) return;
@@ -519,6 +520,35 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, con
                        (int)((int64_t)D.T * D.k), offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2, (const float*)nullptr, D.F,
                        D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
     if (ev) (void)hipEventRecord(ev[2], c->stream);
+    return hipGetLastError();
+}
+
+__global__ void set_row_range(int32_t* __restrict__ offsets2, int32_t rows) {
+    offsets2[0] = 0;
+    offsets2[1] = rows;
+}
+
+// Dense block-scaled FP8 linear layer: the down-projection kernel with a single "expert" that owns all rows.
+hipError_t launch_linear(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t rows, int32_t K, const uint8_t* Wq,
+                         const float* ws, int32_t NOUT, float* y) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm<false>),
+                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
+        if (e2 != hipSuccess) return e2;
+        attr_set = true;
+    }
+    Work* work = reinterpret_cast<Work*>(c->tiles);
+    int32_t* range = c->flags + 2;                             // {0, rows}
+    int32_t* n_work = c->n_tiles + 2;
+    const int nft = (NOUT + 255) / 256;
+    hipLaunchKernelGGL(set_row_range, dim3(1), dim3(1), 0, c->stream, range, rows);
+    hipLaunchKernelGGL(build_work, dim3(1, 1), dim3(256), 0, c->stream, range, 1, nft, nft, work, work, n_work);
+    const int tiles = (rows + TOK_TILE - 1) / TOK_TILE;
+    const int grid = ((tiles * nft + NXCD - 1) / NXCD) * NXCD;
+    hipLaunchKernelGGL((ffn_gemm<false>), dim3(grid), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, rows, range, work,
+                       n_work, Wq, (const uint8_t*)nullptr, ws, (const float*)nullptr, K, NOUT, (uint8_t*)nullptr,
+                       (float*)nullptr, y);
     return hipGetLastError();
 }
 

@@ -90,7 +90,7 @@ int moe_route(moe_ctx* c, const uint16_t* x, const float* W_r, const float* bias
               int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm, int32_t* inv_perm) {
     if (!c || !x || !W_r || !topk_idx || !topk_w || !offsets || !perm || !inv_perm) return MOE_EINVAL;
     if (k != c->dims.k) return MOE_EINVAL;
-    hipError_t e = launch_route(c, x, W_r, bias, topk_idx, topk_w);
+    hipError_t e = launch_route(c, x, W_r, bias, nullptr, topk_idx, topk_w);
     if (e != hipSuccess) return MOE_EHIP;
     return hip_rc(launch_permute(c, topk_idx, nullptr, nullptr, nullptr, offsets, perm, inv_perm));
 }
@@ -104,6 +104,14 @@ int moe_route_replay(moe_ctx* c, const uint16_t* x, const int32_t* logged_idx, c
     int32_t* idx_copy = (topk_idx == logged_idx) ? nullptr : topk_idx;
     float* w_copy = (topk_w == logged_w) ? nullptr : topk_w;
     return hip_rc(launch_permute(c, logged_idx, idx_copy, logged_w, w_copy, offsets, perm, inv_perm));
+}
+
+int moe_route_replay_ids(moe_ctx* c, const uint16_t* x, const float* W_r, const int32_t* logged_idx,
+                         int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm, int32_t* inv_perm) {
+    if (!c || !x || !W_r || !logged_idx || !topk_idx || !topk_w || !offsets || !perm || !inv_perm) return MOE_EINVAL;
+    hipError_t e = launch_route(c, x, W_r, nullptr, logged_idx, topk_idx, topk_w);
+    if (e != hipSuccess) return MOE_EHIP;
+    return hip_rc(launch_permute(c, topk_idx, nullptr, nullptr, nullptr, offsets, perm, inv_perm));
 }
 
 int moe_check_ids(moe_ctx* c) {
@@ -126,6 +134,24 @@ int moe_quantize_fp8(moe_ctx* c, const uint16_t* x, int64_t rows_in, int32_t col
     if (rows_in * (int64_t)fanout > (int64_t)1 << 30) return MOE_EINVAL;
     if (rows_in == 0) return MOE_OK;
     return hip_rc(launch_quantize(c->stream, x, rows_in, cols, dst_rows, fanout, q, scales));
+}
+
+int moe_quantize_weights_fp8(moe_ctx* c, const uint16_t* w, int64_t rows, int32_t cols, uint8_t* q, float* scales) {
+    if (!c || !w || !q || !scales) return MOE_EINVAL;
+    if (rows < 0 || cols <= 0 || rows % QBLOCK || cols % QBLOCK || rows / QBLOCK > 65535) return MOE_EINVAL;
+    if (rows == 0) return MOE_OK;
+    return hip_rc(launch_quantize_weights(c->stream, w, rows, cols, q, scales));
+}
+
+int moe_linear_fp8(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t rows, int32_t K, const uint8_t* Wq,
+                   const float* ws, int32_t NOUT, float* y) {
+    if (!c || !xq || !xs || !Wq || !ws || !y) return MOE_EINVAL;
+    if (rows < 0 || K <= 0 || NOUT <= 0 || K % QBLOCK || NOUT % QBLOCK) return MOE_EINVAL;
+    const int64_t units = ((int64_t)rows + TOK_TILE - 1) / TOK_TILE * ((NOUT + 255) / 256);
+    const int64_t room = (int64_t)c->max_tiles * (c->dims.F / 128 + (c->dims.d + 255) / 256);
+    if (units > room) return MOE_EINVAL;              // the context's work-list storage bounds the problem size
+    if (rows == 0) return MOE_OK;
+    return hip_rc(launch_linear(c, xq, xs, rows, K, Wq, ws, NOUT, y));
 }
 
 int moe_expert_ffn_fp8(moe_ctx* c, const uint8_t* xq, const float* xs, const int32_t* offsets,

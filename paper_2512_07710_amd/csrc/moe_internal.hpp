@@ -37,8 +37,9 @@ struct moe_ctx {
 
 namespace moe355 {
 
+// logged_idx == nullptr: top-k selection; otherwise the ids are given and only the gate weights are computed
 hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const float* bias,
-                        int32_t* topk_idx, float* topk_w);
+                        const int32_t* logged_idx, int32_t* topk_idx, float* topk_w);
 hipError_t launch_permute(moe_ctx* c, const int32_t* ids_in, int32_t* ids_copy, const float* w_in,
                           float* w_copy, int32_t* offsets, int32_t* perm, int32_t* inv_perm);
 hipError_t launch_quantize(hipStream_t s, const uint16_t* x, int64_t rows_in, int32_t cols,
@@ -46,6 +47,10 @@ hipError_t launch_quantize(hipStream_t s, const uint16_t* x, int64_t rows_in, in
 hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, const int32_t* offsets,
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2,
                              const float* s1, const float* s3, const float* s2, float* y_perm);
+hipError_t launch_linear(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t rows, int32_t K,
+                         const uint8_t* Wq, const float* ws, int32_t NOUT, float* y);
+hipError_t launch_quantize_weights(hipStream_t s, const uint16_t* w, int64_t rows, int32_t cols, uint8_t* q,
+                                   float* scales);
 size_t ffn_work_bytes(int max_tiles, int F, int d);
 size_t route_workspace_bytes(int E, int d);
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm,

@@ -69,12 +69,15 @@ __global__ __launch_bounds__(256) void split_router_weights(const float* __restr
     }
 }
 
-// NS: 32-expert sub-tiles per wave (E_pad = 128*NS)
-template <int NS>
+// NS: 32-expert sub-tiles per wave (E_pad = 128*NS).
+// IDS = false: top-k selection.  IDS = true (ids-only Router Replay): the k expert ids of every token are
+// given in logged_idx; their logits are picked out of the same accumulators and only the softmax is new.
+template <int NS, bool IDS>
 __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __restrict__ x,
                                                             const uint16_t* __restrict__ planes,
-                                                            const float* __restrict__ bias, int T, int d, int E,
-                                                            int k, int32_t* __restrict__ topk_idx,
+                                                            const float* __restrict__ bias,
+                                                            const int32_t* __restrict__ logged_idx, int T, int d,
+                                                            int E, int k, int32_t* __restrict__ topk_idx,
                                                             float* __restrict__ topk_w) {
     // two activation stages of 128 rows x 128 bytes; the candidate lists [token][wave][MAX_K]
     // of {logit, expert id} reuse the storage afterwards
@@ -187,6 +190,43 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __syncthreads();                                           // all reads of the activation stages are done
 
+    if (IDS) {
+        // every lane looks up the logged ids of its four tokens among the experts it holds
+        float* sel = reinterpret_cast<float*>(smem);           // [RT][MAX_K] logits of the logged ids
+        for (int i = tid; i < RT * MAX_K; i += 256) sel[i] = 0.f;   // ids outside [0,E) keep logit 0
+        __syncthreads();
+#pragma unroll
+        for (int ts = 0; ts < 4; ++ts) {
+            const int tok = ts * 32 + l32;
+            if (t0 + tok >= T) continue;
+            const int32_t* ids = logged_idx + (size_t)(t0 + tok) * k;
+            for (int j = 0; j < k; ++j) {
+                const int id = ids[j];
+#pragma unroll
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int e = (wave * NS + s) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+                        if (e == id && e < E) sel[tok * MAX_K + j] = acc[s][ts][r];
+                    }
+            }
+        }
+        __syncthreads();
+        if (tid < RT && t0 + tid < T) {
+            const int32_t* ids = logged_idx + (size_t)(t0 + tid) * k;
+            float lg[MAX_K];
+            float m = -INFINITY;
+            for (int j = 0; j < k; ++j) { lg[j] = sel[tid * MAX_K + j]; m = fmaxf(m, lg[j]); }
+            float sum = 0.f;
+            for (int j = 0; j < k; ++j) { lg[j] = expf(lg[j] - m); sum += lg[j]; }
+            for (int j = 0; j < k; ++j) {
+                topk_idx[(size_t)(t0 + tid) * k + j] = ids[j];
+                topk_w[(size_t)(t0 + tid) * k + j] = lg[j] / sum;
+            }
+        }
+        return;
+    }
+
     // ---- per-wave top-k.  Lane (l32, half) holds, for token ts*32+l32, the logits of experts
     //      wave*32*NS + s*32 + (r/4)*8 + half*4 + (r%4).  Candidates: cand[token][wave][j] = {logit, idx}
     float2* cand = reinterpret_cast<float2*>(smem);
@@ -273,7 +313,7 @@ size_t route_workspace_bytes(int E, int d) {
 }
 
 hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const float* bias,
-                        int32_t* topk_idx, float* topk_w) {
+                        const int32_t* logged_idx, int32_t* topk_idx, float* topk_w) {
     const moe_dims& D = c->dims;
     if (D.T == 0) return hipSuccess;
     const int E_pad = D.E <= 128 ? 128 : 256;
@@ -281,12 +321,15 @@ hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const f
     hipLaunchKernelGGL(split_router_weights, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, c->stream,
                        W_r, D.E, E_pad, D.d, c->router_planes);
     const int grid = (D.T + RT - 1) / RT;
-    if (E_pad == 128)
-        hipLaunchKernelGGL((route_mfma_kernel<1>), dim3(grid), dim3(256), 0, c->stream, x, c->router_planes, bias,
-                           D.T, D.d, D.E, D.k, topk_idx, topk_w);
-    else
-        hipLaunchKernelGGL((route_mfma_kernel<2>), dim3(grid), dim3(256), 0, c->stream, x, c->router_planes, bias,
-                           D.T, D.d, D.E, D.k, topk_idx, topk_w);
+#define MOE_ROUTE_LAUNCH(NS_, IDS_)                                                                             \
+    hipLaunchKernelGGL((route_mfma_kernel<NS_, IDS_>), dim3(grid), dim3(256), 0, c->stream, x, c->router_planes, \
+                       bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w)
+    if (E_pad == 128) {
+        if (logged_idx) MOE_ROUTE_LAUNCH(1, true); else MOE_ROUTE_LAUNCH(1, false);
+    } else {
+        if (logged_idx) MOE_ROUTE_LAUNCH(2, true); else MOE_ROUTE_LAUNCH(2, false);
+    }
+#undef MOE_ROUTE_LAUNCH
     return hipGetLastError();
 }
 

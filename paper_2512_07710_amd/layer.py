@@ -54,6 +54,10 @@ class MoELayer:
         B.moe_route_replay(self.ctx, x, logged_idx, logged_w, self.topk_idx, self.topk_w, self.offsets,
                            self.perm, self.inv_perm)
 
+    def route_replay_ids(self, x, W_r, logged_idx):
+        B.moe_route_replay_ids(self.ctx, x, W_r, logged_idx, self.topk_idx, self.topk_w, self.offsets, self.perm,
+                               self.inv_perm)
+
     def quantize(self, x):
         B.moe_quantize_fp8(self.ctx, x, self.T, self.d, 128, self.inv_perm, self.k, self.xq, self.xs)
 

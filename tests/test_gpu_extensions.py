@@ -1,0 +1,165 @@
+"""GPU parity of the entry points beyond the five core calls: ids-only Router Replay, block-wise weight
+quantisation and the dense FP8 linear layer, each against the CPU oracle through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import fp_formats as ff
+from oracle import moe_layer as om
+from workloads import CONFIGS, MoEConfig, make_inputs
+
+pytestmark = pytest.mark.gpu
+
+
+def _bits(x):
+    return x.cpu().view(torch.int16).numpy().view(np.uint16)
+
+
+def _rel_l2(a, b):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
+
+
+@pytest.fixture(scope="module")
+def gpu_lib():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2512_07710_amd as moe
+    moe.load_library()
+    return moe
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS[0], CONFIGS[1],
+                                 MoEConfig("ids_ragged", T=333, d=384, E=40, k=5, F=128, modes=("replay",), seed=21),
+                                 MoEConfig("ids_wide", T=200, d=256, E=200, k=16, F=128, modes=("replay",), seed=22)],
+                         ids=lambda c: c.name)
+def test_replay_ids_recomputes_weights_over_logged_ids(gpu_lib, cfg):
+    """Ids verbatim, permutation bit-exact, weights = softmax of this engine's logits over the logged ids."""
+    inp = make_inputs(cfg, with_experts=False)
+    x, W_r = inp["x"], inp["W_r"]
+    rng = np.random.default_rng(cfg.seed + 100)
+    # a log that is NOT what the router would choose: random distinct experts per token
+    log = np.stack([rng.permutation(cfg.E)[:cfg.k] for _ in range(cfg.T)]).astype(np.int32)
+    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+    try:
+        layer.route_replay_ids(x.cuda(), W_r.cuda(), torch.from_numpy(log).cuda())
+        torch.cuda.synchronize()
+        assert gpu_lib.moe_check_ids(layer.ctx) == 0
+        idx_o, w_o, _ = om.route_replay_ids(_bits(x), W_r.numpy(), log)
+        assert np.array_equal(layer.topk_idx.cpu().numpy(), log)
+        w_g = layer.topk_w.cpu().numpy()
+        assert np.all(np.abs(w_g - w_o) <= 1e-6 + 1e-5 * w_o), float(np.abs(w_g - w_o).max())
+        offsets, perm, inv_perm = om.permute(log, cfg.E)
+        assert np.array_equal(layer.offsets.cpu().numpy(), offsets)
+        assert np.array_equal(layer.perm.cpu().numpy()[:cfg.N], perm)
+        assert np.array_equal(layer.inv_perm.cpu().numpy()[:cfg.N], inv_perm)
+        # logging the router's own decision reproduces the routed weights bit for bit
+        layer.route(x.cuda(), W_r.cuda(), None)
+        torch.cuda.synchronize()
+        r_idx, r_w = layer.topk_idx.clone(), layer.topk_w.clone()
+        layer.route_replay_ids(x.cuda(), W_r.cuda(), r_idx)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.topk_idx, r_idx)
+        assert torch.equal(layer.topk_w.view(torch.int32), r_w.view(torch.int32))
+    finally:
+        layer.close()
+
+
+def test_replay_ids_flags_bad_ids(gpu_lib):
+    cfg = MoEConfig("ids_bad", T=16, d=128, E=4, k=2, F=128, modes=("replay",))
+    inp = make_inputs(cfg, with_experts=False)
+    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+    try:
+        idx = torch.randint(0, 4, (16, 2), dtype=torch.int32)
+        idx[3, 0] = 7
+        layer.route_replay_ids(inp["x"].cuda(), inp["W_r"].cuda(), idx.cuda())
+        assert gpu_lib.moe_check_ids(layer.ctx) == -3
+        assert torch.isfinite(layer.topk_w).all()
+    finally:
+        layer.close()
+
+
+@pytest.mark.parametrize("shape", [(128, 128), (384, 640), (1024, 7168)])
+def test_weight_quantisation_is_bit_exact(gpu_lib, shape):
+    R, C = shape
+    g = torch.Generator().manual_seed(R * 7 + C)
+    w = torch.randn((R, C), generator=g) / C ** 0.5
+    w[:128, :128] *= torch.exp2(torch.randint(-10, 10, (128, 1), generator=g).float())
+    if R > 128:
+        w[128:256, :128] = 0                                  # an all-zero block
+    w[5, 17] = 3.0e38                                          # saturating outlier owns its block
+    wb = w.to(torch.bfloat16)
+    layer = gpu_lib.MoELayer(1, 128, 1, 1, 128)
+    try:
+        q = torch.empty((R, C), dtype=torch.uint8, device="cuda")
+        s = torch.empty((R // 128, C // 128), dtype=torch.float32, device="cuda")
+        gpu_lib.moe_quantize_weights_fp8(layer.ctx, wb.cuda(), R, C, q, s)
+        torch.cuda.synchronize()
+        q_o, s_o = om.quantize_blocks(ff.bf16_bits_to_f64(_bits(wb)))
+        assert np.array_equal(s.cpu().numpy(), s_o)
+        assert np.array_equal(q.cpu().numpy(), q_o)
+        with pytest.raises(gpu_lib.MoEError):
+            gpu_lib.moe_quantize_weights_fp8(layer.ctx, wb.cuda(), R, C - 64, q, s)
+    finally:
+        layer.close()
+
+
+def test_weight_quantisation_feeds_the_expert_ffn(gpu_lib):
+    """bf16 expert weights -> moe_quantize_weights_fp8 -> moe_expert_ffn_fp8: the weight-update path end to end."""
+    cfg = MoEConfig("wq_e2e", T=96, d=256, E=4, k=2, F=256, modes=("routed",), seed=31)
+    g = torch.Generator().manual_seed(31)
+    x = torch.randn((cfg.T, cfg.d), generator=g).to(torch.bfloat16)
+    W_r = torch.randn((cfg.E, cfg.d), generator=g) / cfg.d ** 0.5
+    Wb = {n: (torch.randn(shape, generator=g) / cfg.d ** 0.5).to(torch.bfloat16)
+          for n, shape in (("W1", (cfg.E, cfg.F, cfg.d)), ("W3", (cfg.E, cfg.F, cfg.d)), ("W2", (cfg.E, cfg.d, cfg.F)))}
+    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+    try:
+        dev, host = {}, {}
+        for n, w in Wb.items():
+            rows, cols = w.shape[0] * w.shape[1], w.shape[2]
+            q = torch.empty(w.shape, dtype=torch.uint8, device="cuda")
+            s = torch.empty((w.shape[0], w.shape[1] // 128, cols // 128), dtype=torch.float32, device="cuda")
+            gpu_lib.moe_quantize_weights_fp8(layer.ctx, w.cuda(), rows, cols, q, s)
+            q_o, s_o = om.quantize_blocks(ff.bf16_bits_to_f64(_bits(w.reshape(rows, cols))))
+            assert np.array_equal(q.cpu().numpy().reshape(rows, cols), q_o)
+            assert np.array_equal(s.cpu().numpy().reshape(rows // 128, cols // 128), s_o)
+            dev[n + "q"], dev["s" + n[1]] = q, s
+            host[n + "q"], host["s" + n[1]] = q_o.reshape(w.shape), s_o.reshape(s.shape)
+        layer.forward_routed(x.cuda(), W_r.cuda(), None, dev)
+        torch.cuda.synchronize()
+        ref = om.moe_layer(_bits(x), cfg.E, layer.topk_idx.cpu().numpy(), layer.topk_w.cpu().numpy(),
+                           host["W1q"], host["W3q"], host["W2q"], host["s1"], host["s3"], host["s2"])
+        rel = _rel_l2(layer.y.float().cpu().numpy(), ff.bf16_bits_to_f64(ref["y_bits"]))
+        print(f"[wq_e2e] layer rel-L2 {rel:.3e}")
+        assert rel <= 2e-3
+    finally:
+        layer.close()
+
+
+@pytest.mark.parametrize("rows,K,NOUT", [(300, 256, 384), (1, 128, 128), (777, 1024, 640), (2048, 512, 1280)])
+def test_dense_linear_matches_block_scaled_matmul(gpu_lib, rows, K, NOUT):
+    g = torch.Generator().manual_seed(rows + K + NOUT)
+    x = torch.randn((rows, K), generator=g).to(torch.bfloat16)
+    w = (torch.randn((NOUT, K), generator=g) / K ** 0.5).to(torch.bfloat16)
+    layer = gpu_lib.MoELayer(2048, 1280, 4, 2, 1280)          # its work-list storage bounds the linear's size
+    try:
+        xq = torch.empty((rows, K), dtype=torch.uint8, device="cuda")
+        xs = torch.empty((K // 128, rows), dtype=torch.float32, device="cuda")
+        gpu_lib.moe_quantize_fp8(layer.ctx, x.cuda(), rows, K, 128, None, 1, xq, xs)
+        wq = torch.empty((NOUT, K), dtype=torch.uint8, device="cuda")
+        ws = torch.empty((NOUT // 128, K // 128), dtype=torch.float32, device="cuda")
+        gpu_lib.moe_quantize_weights_fp8(layer.ctx, w.cuda(), NOUT, K, wq, ws)
+        y = torch.full((rows, NOUT), float("nan"), dtype=torch.float32, device="cuda")
+        gpu_lib.moe_linear_fp8(layer.ctx, xq, xs, rows, K, wq, ws, NOUT, y)
+        torch.cuda.synchronize()
+        xq_o, xs_o = om.quantize_rows(ff.bf16_bits_to_f64(_bits(x)))
+        wq_o, ws_o = om.quantize_blocks(ff.bf16_bits_to_f64(_bits(w)))
+        assert np.array_equal(xq.cpu().numpy(), xq_o) and np.array_equal(xs.cpu().numpy().T, xs_o)
+        assert np.array_equal(wq.cpu().numpy(), wq_o) and np.array_equal(ws.cpu().numpy(), ws_o)
+        y_o = om.block_scaled_matmul(xq_o, xs_o, wq_o, ws_o)
+        rel = _rel_l2(y.cpu().numpy(), y_o)
+        print(f"[linear {rows}x{K}x{NOUT}] rel-L2 {rel:.3e}")
+        assert rel <= 1e-4                                    # fp32 accumulation + the matrix pipe's own rounding
+        with pytest.raises(gpu_lib.MoEError):
+            gpu_lib.moe_linear_fp8(layer.ctx, xq, xs, rows, K - 64, wq, ws, NOUT, y)
+    finally:
+        layer.close()
