@@ -151,19 +151,23 @@ def main() -> int:
         "route_replay": stage_ms(lambda: layer.route_replay(x, log_idx, log_w)),
     }
     (step_routed if head_mode == "routed" else step_replay)()
-    stages["quantize"] = stage_ms(lambda: layer.quantize(x))
-    stages["expert_ffn"] = stage_ms(lambda: layer.expert_ffn(inp))
+    stages["quantize"] = stage_ms(lambda: layer.quantize_tokens(x))          # once per token (the timed path)
+    stages["expert_ffn"] = stage_ms(lambda: layer.expert_ffn_gather(inp))     # gathers inside the gate/up GEMM
     stages["combine"] = stage_ms(layer.combine)
+    # the unfused alternative: expert-ordered copy of the activations, then the plain grouped FFN
+    stages["quantize_fanout_unfused"] = stage_ms(lambda: layer.quantize(x))
+    stages["expert_ffn_unfused"] = stage_ms(lambda: layer.expert_ffn(inp))
 
     N, d, F, T, k = cfg.N, cfg.d, cfg.F, cfg.T, cfg.k
     flop = 6.0 * N * d * F
     gemm1_flop = 4.0 * N * d * F
-    q_bytes = 2.0 * T * d + N * d + 4.0 * N * d / 128
+    q_bytes = 2.0 * T * d + T * d + 4.0 * T * d / 128          # token-order quantisation: read bf16, write codes + scales
+    qf_bytes = 2.0 * T * d + N * d + 4.0 * N * d / 128         # with the k-fold fan-out of the unfused path
     c_bytes = 4.0 * N * d + 8.0 * N + 2.0 * T * d
-    roof = {"bound": "mfma", "kernel": "ffn_gemm<gate/up> (GEMM1 + SwiGLU + h re-quantisation)",
+    roof = {"bound": "mfma", "kernel": "ffn_gemm<gate/up, gather> (token gather + GEMM1 + SwiGLU + h re-quantisation)",
             "achieved": gemm1_flop / (g1 * 1e-3) / 1e12, "peak": FP8_PEAK_TFLOPS, "unit": "TFLOP/s",
             "frac": gemm1_flop / (g1 * 1e-3) / 1e12 / FP8_PEAK_TFLOPS, "traffic": _measured_traffic(args.config),
-            "algorithmic_bytes": 2.0 * cfg.E * d * F + N * d + N * F,
+            "algorithmic_bytes": 2.0 * cfg.E * d * F + T * d + N * F,       # weights, token-order codes, hq
             "avg_launch_ms": g1, "flop_per_launch": gemm1_flop}
     out = {
         "metric": "MoE-layer fwd FP8 TFLOP/s (% MFMA peak) + tokens/s, routed vs replay",
@@ -182,6 +186,8 @@ def main() -> int:
         "kernels": {"gemm1_ms": g1, "gemm2_ms": g2,
                     "gemm1_tflops": gemm1_flop / (g1 * 1e-3) / 1e12,
                     "gemm2_tflops": 2.0 * N * d * F / (g2 * 1e-3) / 1e12,
+                    "quantize_fanout_GBs": qf_bytes / (stages["quantize_fanout_unfused"] * 1e-3) / 1e9,
+                    "quantize_fanout_frac_hbm": qf_bytes / (stages["quantize_fanout_unfused"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "quantize_GBs": q_bytes / (stages["quantize"] * 1e-3) / 1e9,
                     "quantize_frac_hbm": q_bytes / (stages["quantize"] * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     "combine_GBs": c_bytes / (stages["combine"] * 1e-3) / 1e9,

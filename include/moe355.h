@@ -152,6 +152,17 @@ int moe_expert_ffn_fp8(moe_ctx* ctx, const uint8_t* xq_perm, const float* xs_per
                        const uint8_t* W2, const float* s1, const float* s3, const float* s2,
                        float* y_perm);
 
+/* The same FFN with the token gather fused into the gate/up GEMM: xq_tok [T,d] u8 and xs_tok [d/128][T] f32
+ * are the activations quantised ONCE per token, in token order (moe_quantize_fp8 with dst_rows = NULL);
+ * expert-sorted row p reads token perm[p]/k through the row -> token map that the last moe_route,
+ * moe_route_replay or moe_route_replay_ids call on this context left in its workspace.  No expert-ordered
+ * copy of the activations exists: the layer saves its k-fold write and re-read.  Results are bit-identical
+ * to moe_expert_ffn_fp8 on the gathered rows.  offsets must be the ones that routing call produced. */
+int moe_expert_ffn_fp8_gather(moe_ctx* ctx, const uint8_t* xq_tok, const float* xs_tok,
+                              const int32_t* offsets, const uint8_t* W1, const uint8_t* W3,
+                              const uint8_t* W2, const float* s1, const float* s3, const float* s2,
+                              float* y_perm);
+
 /* Weighted combine back to token order:
  *   y[t,c] = bf16( sum_{j<k} topk_w[t,j] * y_perm[inv_perm[t*k+j], c] ),
  * fp32 fused multiply-adds in slot order, one rounding to bf16 at the end.

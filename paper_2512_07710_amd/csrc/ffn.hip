@@ -137,9 +137,14 @@ __device__ inline uint32_t pack4_e4m3(float a, float b, float c, float d) {
 // GATED = true : Wa = W1, Wb = W3 [E, NOUT, K]; feature tile = 128 features (gate + up rows)
 // GATED = false: Wa = W2 [E, NOUT, K]; feature tile = 256 output features
 // act [N, K] u8 are the expert-sorted activations; act_s [K/128][N] f32 their scales, K-block major.
-template <bool GATED>
+// GATHER (gate/up only): act [T, K] is in TOKEN order and sorted row p reads the codes of token
+// row_token[p]: the expert-ordered copy of the codes is never materialised.  The scales act_s
+// [K/128][n_rows] are in sorted order in both cases (they are 1/128 of the data; a lane-scattered
+// scale read per K step would cost more than it saves).
+template <bool GATED, bool GATHER>
 __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restrict__ act,
                                                         const float* __restrict__ act_s, int n_rows,
+                                                        const int32_t* __restrict__ row_token,
                                                         const int32_t* __restrict__ offsets,
                                                         const Work* __restrict__ work,
                                                         const int32_t* __restrict__ n_work,
@@ -191,11 +196,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
             int f = GATED ? f0 + (r >> 7) * 64 + (r & 63) : f0 + r;
             f = min(f, NOUT - 1);
             w_off[j] = (uint32_t)f * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
-            const int p = min(wk.row0 + r, row_end - 1) - wk.row0;      // rows past the segment repeat its last row
-            x_off[j] = (uint32_t)p * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
+            const int p = min(wk.row0 + r, row_end - 1);      // rows past the tile repeat its last row
+            const int src = GATHER ? row_token[p] : p - wk.row0;
+            x_off[j] = (uint32_t)src * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
         }
     }
-    const uint8_t* x_base = act + (size_t)wk.row0 * K;
+    const uint8_t* x_base = GATHER ? act : act + (size_t)wk.row0 * K;
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
     const uint32_t lds_rows = lds0 + wave * 32 * KB;           // this wave's rows inside a tile buffer
 
@@ -486,24 +492,43 @@ size_t ffn_work_bytes(int max_tiles, int F, int d) {
     return sizeof(Work) * (size_t)max_tiles * (size_t)(F / 128 + (d + 255) / 256);
 }
 
-hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, const int32_t* offsets,
+static hipError_t set_lds_limits() {
+    static bool attr_set = false;
+    if (attr_set) return hipSuccess;
+    const void* kernels[3] = {reinterpret_cast<const void*>(&ffn_gemm<true, false>),
+                              reinterpret_cast<const void*>(&ffn_gemm<true, true>),
+                              reinterpret_cast<const void*>(&ffn_gemm<false, false>)};
+    for (const void* k : kernels) {
+        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
+        if (e != hipSuccess) return e;
+    }
+    attr_set = true;
+    return hipSuccess;
+}
+
+// scales of the expert-sorted rows from the per-token scales: out[g][p] = in[g][row_token[p]]
+__global__ __launch_bounds__(256) void gather_scales(const float* __restrict__ in, int T, const int32_t* __restrict__ row_token,
+                                                     int N, float* __restrict__ out) {
+    const int p = blockIdx.x * 256 + threadIdx.x;
+    if (p >= N) return;
+    const size_t g = blockIdx.y;
+    out[g * N + p] = in[g * T + row_token[p]];
+}
+
+// gathered == false: xq/xs are the expert-ordered activations [N,d], [d/128][N].
+// gathered == true : xq/xs are in token order [T,d], [d/128][T]; sorted row p reads token c->row_token[p]
+//                    (the scales are first brought into sorted order in the context's workspace).
+hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, bool gathered, const int32_t* offsets,
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2, const float* s1,
                              const float* s3, const float* s2, float* y_perm) {
     const moe_dims& D = c->dims;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e1 = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm<true>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
-        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm<false>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
-        if (e1 != hipSuccess) return e1;
-        if (e2 != hipSuccess) return e2;
-        attr_set = true;
-    }
+    hipError_t ea = set_lds_limits();
+    if (ea != hipSuccess) return ea;
     Work* work = reinterpret_cast<Work*>(c->tiles);
     hipEvent_t* ev = nullptr;
     if (c->profiling && c->prof_calls < PROF_MAX_CALLS) ev = c->prof_events + 3 * c->prof_calls++;
 
+    const int N = (int)((int64_t)D.T * D.k);
     const int nft1 = D.F / 128;
     const int nft2 = (D.d + 255) / 256;
     Work* work2 = work + (size_t)c->max_tiles * nft1;          // the down projection's list
@@ -512,13 +537,22 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, con
                        c->n_tiles);
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     const int grid1 = ((c->max_tiles * nft1 + NXCD - 1) / NXCD) * NXCD;
-    hipLaunchKernelGGL((ffn_gemm<true>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, (int)((int64_t)D.T * D.k), offsets,
-                       work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq, c->hs, (float*)nullptr);
+    if (gathered) {
+        hipLaunchKernelGGL(gather_scales, dim3((N + 255) / 256, D.d / QBLOCK), dim3(256), 0, c->stream, xs, D.T,
+                           c->row_token, N, c->xs_sorted);
+        hipLaunchKernelGGL((ffn_gemm<true, true>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, c->xs_sorted, N,
+                           c->row_token, offsets, work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq, c->hs,
+                           (float*)nullptr);
+    } else {
+        hipLaunchKernelGGL((ffn_gemm<true, false>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, N,
+                           (const int32_t*)nullptr, offsets, work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq,
+                           c->hs, (float*)nullptr);
+    }
     if (ev) (void)hipEventRecord(ev[1], c->stream);
     const int grid2 = ((c->max_tiles * nft2 + NXCD - 1) / NXCD) * NXCD;
-    hipLaunchKernelGGL((ffn_gemm<false>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq, c->hs,
-                       (int)((int64_t)D.T * D.k), offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2, (const float*)nullptr, D.F,
-                       D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
+    hipLaunchKernelGGL((ffn_gemm<false, false>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq, c->hs, N,
+                       (const int32_t*)nullptr, offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2,
+                       (const float*)nullptr, D.F, D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     return hipGetLastError();
 }
@@ -531,13 +565,8 @@ __global__ void set_row_range(int32_t* __restrict__ offsets2, int32_t rows) {
 // Dense block-scaled FP8 linear layer: the down-projection kernel with a single "expert" that owns all rows.
 hipError_t launch_linear(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t rows, int32_t K, const uint8_t* Wq,
                          const float* ws, int32_t NOUT, float* y) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e2 = hipFuncSetAttribute(reinterpret_cast<const void*>(&ffn_gemm<false>),
-                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
-        if (e2 != hipSuccess) return e2;
-        attr_set = true;
-    }
+    hipError_t ea = set_lds_limits();
+    if (ea != hipSuccess) return ea;
     Work* work = reinterpret_cast<Work*>(c->tiles);
     int32_t* range = c->flags + 2;                             // {0, rows}
     int32_t* n_work = c->n_tiles + 2;
@@ -546,8 +575,8 @@ hipError_t launch_linear(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t
     hipLaunchKernelGGL(build_work, dim3(1, 1), dim3(256), 0, c->stream, range, 1, nft, nft, work, work, n_work);
     const int tiles = (rows + TOK_TILE - 1) / TOK_TILE;
     const int grid = ((tiles * nft + NXCD - 1) / NXCD) * NXCD;
-    hipLaunchKernelGGL((ffn_gemm<false>), dim3(grid), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, rows, range, work,
-                       n_work, Wq, (const uint8_t*)nullptr, ws, (const float*)nullptr, K, NOUT, (uint8_t*)nullptr,
+    hipLaunchKernelGGL((ffn_gemm<false, false>), dim3(grid), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, rows,
+                       (const int32_t*)nullptr, range, work, n_work, Wq, (const uint8_t*)nullptr, ws, (const float*)nullptr, K, NOUT, (uint8_t*)nullptr,
                        (float*)nullptr, y);
     return hipGetLastError();
 }

@@ -54,7 +54,10 @@ int moe_create(moe_ctx** out, const moe_dims* dims, void* hip_stream) {
     ok = ok && hipMalloc((void**)&c->tiles, ffn_work_bytes(c->max_tiles, dims->F, dims->d)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->n_tiles, 4 * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->flags, 4 * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->row_token, nrow * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMemsetAsync(c->row_token, 0, nrow * sizeof(int32_t), c->stream) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->router_planes, route_workspace_bytes(dims->E, dims->d)) == hipSuccess;
+    ok = ok && hipMalloc((void**)&c->xs_sorted, nrow * (size_t)(dims->d / QBLOCK) * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hq, nrow * (size_t)dims->F) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hs, nrow * (size_t)(dims->F / QBLOCK) * sizeof(float)) == hipSuccess;
     ok = ok && hipMemsetAsync(c->flags, 0, 4 * sizeof(int32_t), c->stream) == hipSuccess;
@@ -75,6 +78,8 @@ int moe_destroy(moe_ctx* c) {
     if (c->tiles) (void)hipFree(c->tiles);
     if (c->n_tiles) (void)hipFree(c->n_tiles);
     if (c->flags) (void)hipFree(c->flags);
+    if (c->row_token) (void)hipFree(c->row_token);
+    if (c->xs_sorted) (void)hipFree(c->xs_sorted);
     if (c->router_planes) (void)hipFree(c->router_planes);
     if (c->hq) (void)hipFree(c->hq);
     if (c->hs) (void)hipFree(c->hs);
@@ -159,7 +164,15 @@ int moe_expert_ffn_fp8(moe_ctx* c, const uint8_t* xq, const float* xs, const int
                        const float* s3, const float* s2, float* y_perm) {
     if (!c || !xq || !xs || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
     if (c->dims.T == 0) return MOE_OK;
-    return hip_rc(launch_expert_ffn(c, xq, xs, offsets, W1, W3, W2, s1, s3, s2, y_perm));
+    return hip_rc(launch_expert_ffn(c, xq, xs, false, offsets, W1, W3, W2, s1, s3, s2, y_perm));
+}
+
+int moe_expert_ffn_fp8_gather(moe_ctx* c, const uint8_t* xq_tok, const float* xs_tok, const int32_t* offsets,
+                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2, const float* s1,
+                              const float* s3, const float* s2, float* y_perm) {
+    if (!c || !xq_tok || !xs_tok || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
+    if (c->dims.T == 0) return MOE_OK;
+    return hip_rc(launch_expert_ffn(c, xq_tok, xs_tok, true, offsets, W1, W3, W2, s1, s3, s2, y_perm));
 }
 
 int moe_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm, const float* topk_w,

@@ -25,7 +25,9 @@ struct moe_ctx {
     int32_t* chunk_counts;   // [n_chunks][E] per-chunk histograms, then their exclusive scans
     void* tiles;             // GEMM work lists (gate/up list, then down list)
     int32_t* n_tiles;        // [2] their lengths
-    int32_t* flags;          // [4] flags[0] != 0: an expert id outside [0,E) was met
+    int32_t* flags;          // [4] flags[0] != 0: an expert id outside [0,E) was met; [2..3]: row range of a dense linear
+    int32_t* row_token;      // [N] token of every expert-sorted row, written by the last routing call
+    float* xs_sorted;        // [d/128][N] activation scales in sorted order (gathered FFN only)
     uint16_t* router_planes; // router weights split into three bf16 planes, matrix-core order
     uint8_t* hq;             // [N][F]
     float* hs;               // [N][F/128]
@@ -44,7 +46,7 @@ hipError_t launch_permute(moe_ctx* c, const int32_t* ids_in, int32_t* ids_copy, 
                           float* w_copy, int32_t* offsets, int32_t* perm, int32_t* inv_perm);
 hipError_t launch_quantize(hipStream_t s, const uint16_t* x, int64_t rows_in, int32_t cols,
                            const int32_t* dst_rows, int32_t fanout, uint8_t* q, float* scales);
-hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, const int32_t* offsets,
+hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, bool gathered, const int32_t* offsets,
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2,
                              const float* s1, const float* s3, const float* s2, float* y_perm);
 hipError_t launch_linear(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t rows, int32_t K,

@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void scatter(const int32_t* __restrict__ ids, 
                                                const int32_t* __restrict__ offsets,
                                                const float* __restrict__ w_in, float* __restrict__ w_copy,
                                                int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
-                                               int32_t* __restrict__ flags) {
+                                               int32_t* __restrict__ row_token, int k, int32_t* __restrict__ flags) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     if (w_copy) w_copy[i] = w_in[i];
@@ -129,6 +129,7 @@ __global__ __launch_bounds__(256) void scatter(const int32_t* __restrict__ ids, 
     const int pos = offsets[e] + chunk_prefix[(size_t)chunk * E + e] + inv_perm[i];   // inv_perm holds the rank
     inv_perm[i] = pos;
     perm[pos] = i;
+    row_token[pos] = i / k;                             // read by the gathering gate/up GEMM
 }
 
 }  // namespace
@@ -145,7 +146,7 @@ hipError_t launch_permute(moe_ctx* c, const int32_t* ids_in, int32_t* ids_copy, 
                        offsets);
     if (N > 0)
         hipLaunchKernelGGL(scatter, dim3((N + 255) / 256), dim3(256), 0, c->stream, ids_in, N, D.E,
-                           c->chunk_counts, offsets, w_in, w_copy, perm, inv_perm, c->flags);
+                           c->chunk_counts, offsets, w_in, w_copy, perm, inv_perm, c->row_token, D.k, c->flags);
     return hipGetLastError();
 }
 

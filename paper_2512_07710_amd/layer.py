@@ -31,6 +31,8 @@ class MoELayer:
         self.inv_perm = torch.empty((N,), dtype=torch.int32, device=dev)
         self.xq = torch.empty((N, d), dtype=torch.uint8, device=dev)
         self.xs = torch.empty((d // 128, N), dtype=torch.float32, device=dev)   # group-major scale planes
+        self.xq_tok = torch.empty((max(T, 1), d), dtype=torch.uint8, device=dev)       # token order, quantised once
+        self.xs_tok = torch.empty((d // 128, max(T, 1)), dtype=torch.float32, device=dev)
         self.y_perm = torch.empty((N, d), dtype=torch.float32, device=dev)
         self.y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
 
@@ -61,6 +63,13 @@ class MoELayer:
     def quantize(self, x):
         B.moe_quantize_fp8(self.ctx, x, self.T, self.d, 128, self.inv_perm, self.k, self.xq, self.xs)
 
+    def quantize_tokens(self, x):
+        B.moe_quantize_fp8(self.ctx, x, self.T, self.d, 128, None, 1, self.xq_tok, self.xs_tok)
+
+    def expert_ffn_gather(self, w: Dict[str, torch.Tensor]):
+        B.moe_expert_ffn_fp8_gather(self.ctx, self.xq_tok, self.xs_tok, self.offsets, w["W1q"], w["W3q"], w["W2q"],
+                                    w["s1"], w["s3"], w["s2"], self.y_perm)
+
     def expert_ffn(self, w: Dict[str, torch.Tensor]):
         B.moe_expert_ffn_fp8(self.ctx, self.xq, self.xs, self.offsets, w["W1q"], w["W3q"], w["W2q"], w["s1"],
                              w["s3"], w["s2"], self.y_perm)
@@ -69,19 +78,25 @@ class MoELayer:
         B.moe_combine(self.ctx, self.y_perm, self.inv_perm, self.topk_w, self.y)
 
     # ---- whole layer ----------------------------------------------------------------
-    def forward_routed(self, x, W_r, sel_bias, w):
-        self.route(x, W_r, sel_bias)
-        self.quantize(x)
-        self.expert_ffn(w)
+    # `fused` = True: activations quantised once per token, gathered inside the gate/up GEMM;
+    # False: the expert-ordered copy xq/xs is materialised first (same results bit for bit)
+    def _ffn(self, x, w, fused):
+        if fused:
+            self.quantize_tokens(x)
+            self.expert_ffn_gather(w)
+        else:
+            self.quantize(x)
+            self.expert_ffn(w)
         self.combine()
         return self.y
 
-    def forward_replay(self, x, logged_idx, logged_w, w):
+    def forward_routed(self, x, W_r, sel_bias, w, fused=True):
+        self.route(x, W_r, sel_bias)
+        return self._ffn(x, w, fused)
+
+    def forward_replay(self, x, logged_idx, logged_w, w, fused=True):
         self.route_replay(x, logged_idx, logged_w)
-        self.quantize(x)
-        self.expert_ffn(w)
-        self.combine()
-        return self.y
+        return self._ffn(x, w, fused)
 
     def hidden(self):
         """Copies of (hq [N,F] u8, hs [F/128,N] f32, group-major) written by the last expert_ffn call."""

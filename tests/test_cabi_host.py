@@ -61,6 +61,7 @@ def test_null_arguments_are_rejected(lib):
     assert lib.moe_route_replay_ids(None, None, None, None, None, None, None, None, None) == -1
     assert lib.moe_quantize_weights_fp8(None, None, 128, 128, None, None) == -1
     assert lib.moe_linear_fp8(None, None, None, 4, 128, None, None, 128, None) == -1
+    assert lib.moe_expert_ffn_fp8_gather(None, None, None, None, None, None, None, None, None, None, None) == -1
     assert lib.moe_expert_ffn_fp8(*([None] * 11)) == -1
     assert lib.moe_combine(*([None] * 5)) == -1
     assert lib.moe_check_ids(None) == -1

@@ -163,3 +163,38 @@ def test_dense_linear_matches_block_scaled_matmul(gpu_lib, rows, K, NOUT):
             gpu_lib.moe_linear_fp8(layer.ctx, xq, xs, rows, K - 64, wq, ws, NOUT, y)
     finally:
         layer.close()
+
+
+@pytest.mark.parametrize("cfg", [CONFIGS[0], CONFIGS[1],
+                                 MoEConfig("g_ragged", T=333, d=384, E=40, k=5, F=384, modes=("routed",), seed=41),
+                                 MoEConfig("g_skew", T=900, d=256, E=6, k=2, F=256, modes=("routed",), seed=42)],
+                         ids=lambda c: c.name)
+def test_gather_fused_ffn_is_bit_identical_to_the_materialised_path(gpu_lib, cfg):
+    """Token-order activations gathered inside the gate/up GEMM: same hq/hs/y_perm/y as with the expert-ordered copy."""
+    inp = make_inputs(cfg)
+    dv = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in inp.items()}
+    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+    try:
+        layer.forward_routed(dv["x"], dv["W_r"], None, dv, fused=False)
+        torch.cuda.synchronize()
+        hq_a, hs_a = [t.clone() for t in layer.hidden()]
+        yp_a, y_a = layer.y_perm.clone(), layer.y.clone()
+        layer.y_perm.zero_(); layer.y.zero_()
+        layer.forward_routed(dv["x"], dv["W_r"], None, dv, fused=True)
+        torch.cuda.synchronize()
+        hq_b, hs_b = layer.hidden()
+        # token-order quantisation against the oracle, bit for bit
+        xq_o, xs_o = om.quantize_rows(ff.bf16_bits_to_f64(_bits(inp["x"])))
+        assert np.array_equal(layer.xq_tok.cpu().numpy(), xq_o)
+        assert np.array_equal(layer.xs_tok.cpu().numpy().T, xs_o)
+        assert torch.equal(hq_a, hq_b) and torch.equal(hs_a.view(torch.int32), hs_b.view(torch.int32))
+        assert torch.equal(yp_a.view(torch.int32), layer.y_perm.view(torch.int32))
+        assert torch.equal(y_a.view(torch.int16), layer.y.view(torch.int16))
+        # and the layer output against the oracle
+        ref = om.moe_layer(_bits(inp["x"]), cfg.E, layer.topk_idx.cpu().numpy(), layer.topk_w.cpu().numpy(),
+                           *[inp[n].numpy() for n in ("W1q", "W3q", "W2q", "s1", "s3", "s2")])
+        rel = _rel_l2(layer.y.float().cpu().numpy(), ff.bf16_bits_to_f64(ref["y_bits"]))
+        print(f"[{cfg.name}] gather-fused layer rel-L2 {rel:.3e}")
+        assert rel <= 2e-3
+    finally:
+        layer.close()

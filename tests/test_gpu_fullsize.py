@@ -54,7 +54,7 @@ def _fullsize(gpu_lib, cfg, mode, n_tokens_e2e):
         x_bits = _bits(inp["x"])
         bias = inp["sel_bias"].cpu().numpy() if inp.get("sel_bias") is not None else None
         if mode == "routed":
-            layer.forward_routed(inp["x"], inp["W_r"], inp.get("sel_bias"), inp)
+            layer.forward_routed(inp["x"], inp["W_r"], inp.get("sel_bias"), inp, fused=False)
             torch.cuda.synchronize()
             _check_routing_full(cfg, x_bits, inp["W_r"].cpu().numpy(), bias, layer.topk_idx.cpu().numpy(),
                                 layer.topk_w.cpu().numpy())
@@ -64,7 +64,7 @@ def _fullsize(gpu_lib, cfg, mode, n_tokens_e2e):
             else:   # the oracle's own routing decision serves as the log
                 oi, ow, _ = om.route(x_bits, inp["W_r"].cpu().numpy(), cfg.k, bias)
                 log_idx, log_w = torch.from_numpy(oi).to(dev), torch.from_numpy(ow).to(dev)
-            layer.forward_replay(inp["x"], log_idx, log_w, inp)
+            layer.forward_replay(inp["x"], log_idx, log_w, inp, fused=False)
             torch.cuda.synchronize()
             assert torch.equal(layer.topk_idx, log_idx) and torch.equal(layer.topk_w, log_w)
         assert gpu_lib.moe_check_ids(layer.ctx) == 0
@@ -151,7 +151,16 @@ def _fullsize(gpu_lib, cfg, mode, n_tokens_e2e):
               f"(bar {REL_L2_BAR}, whole tensor), per-token max {np.sqrt(num_t / np.sum(ref ** 2, axis=1)).max():.3e}")
         # the bar is a whole-tensor figure; a token sample may not exceed it by more than its sampling error
         assert est - 2.0 * se <= REL_L2_BAR
-        # replay must follow the log: sampled rows of y_perm belong to the logged expert
+        # the gather-fused path (activations quantised once per token, gathered inside the gate/up GEMM) must
+        # reproduce the materialised path bit for bit at full size
+        y_mat = layer.y.clone()
+        hq_mat, hs_mat = layer.hidden()
+        layer.y.zero_()
+        layer._ffn(inp["x"], inp, fused=True)
+        torch.cuda.synchronize()
+        hq_f, hs_f = layer.hidden()
+        assert torch.equal(hq_mat, hq_f) and torch.equal(hs_mat.view(torch.int32), hs_f.view(torch.int32))
+        assert torch.equal(y_mat.view(torch.int16), layer.y.view(torch.int16))
         return layer.y.clone()
     finally:
         layer.close()

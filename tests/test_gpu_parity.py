@@ -163,19 +163,21 @@ def test_config0_routed(gpu_lib):
 
 
 def _replay_of_own_routing_is_bitwise_identical(gpu_lib, cfg):
-    """Replay fed with the GPU's own routed ids and weights must reproduce every output bit."""
+    """Replay fed with the GPU's own routed ids and weights must reproduce every output bit, on both FFN paths."""
     inp = _dev(make_inputs(cfg))
     layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
     try:
-        layer.forward_routed(inp["x"], inp["W_r"], inp.get("sel_bias"), inp)
-        torch.cuda.synchronize()
-        keep = {n: getattr(layer, n).clone() for n in ("topk_idx", "topk_w", "offsets", "perm", "inv_perm", "xq", "xs", "y_perm", "y")}
-        for n in ("offsets", "perm", "inv_perm", "xq", "y_perm", "y"):
-            getattr(layer, n).zero_()
-        layer.forward_replay(inp["x"], keep["topk_idx"], keep["topk_w"], inp)
-        torch.cuda.synchronize()
-        for n, v in keep.items():
-            assert torch.equal(getattr(layer, n).view(torch.uint8), v.view(torch.uint8)), n
+        for fused in (False, True):
+            acts = ("xq_tok", "xs_tok") if fused else ("xq", "xs")
+            layer.forward_routed(inp["x"], inp["W_r"], inp.get("sel_bias"), inp, fused=fused)
+            torch.cuda.synchronize()
+            keep = {n: getattr(layer, n).clone() for n in ("topk_idx", "topk_w", "offsets", "perm", "inv_perm", "y_perm", "y") + acts}
+            for n in ("offsets", "perm", "inv_perm", "y_perm", "y") + acts:
+                getattr(layer, n).zero_()
+            layer.forward_replay(inp["x"], keep["topk_idx"], keep["topk_w"], inp, fused=fused)
+            torch.cuda.synchronize()
+            for n, v in keep.items():
+                assert torch.equal(getattr(layer, n).view(torch.uint8), v.view(torch.uint8)), (n, fused)
     finally:
         layer.close()
 
