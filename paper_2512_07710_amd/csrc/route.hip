@@ -22,7 +22,6 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int RT = 128;          // tokens per block
 constexpr int RKC = 64;          // hidden columns per staged activation chunk (128 bytes per row)
 constexpr int NO_CAND = 0x7FFFFFFF;
 
@@ -69,17 +68,19 @@ __global__ __launch_bounds__(256) void split_router_weights(const float* __restr
     }
 }
 
-// NS: 32-expert sub-tiles per wave (E_pad = 128*NS).
+// NS: 32-expert sub-tiles per wave (E_pad = 128*NS).  TS: 32-token sub-tiles per block (32*TS tokens):
+// four for large batches, one when the batch would otherwise fill only a fraction of the compute units.
 // IDS = false: top-k selection.  IDS = true (ids-only Router Replay): the k expert ids of every token are
 // given in logged_idx; their logits are picked out of the same accumulators and only the softmax is new.
-template <int NS, bool IDS>
+template <int NS, int TS, bool IDS>
 __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __restrict__ x,
                                                             const uint16_t* __restrict__ planes,
                                                             const float* __restrict__ bias,
                                                             const int32_t* __restrict__ logged_idx, int T, int d,
                                                             int E, int k, int32_t* __restrict__ topk_idx,
                                                             float* __restrict__ topk_w) {
-    // two activation stages of 128 rows x 128 bytes; the candidate lists [token][wave][MAX_K]
+    constexpr int RT = 32 * TS;                                // tokens per block
+    // two activation stages of RT rows x 128 bytes; the candidate lists [token][wave][MAX_K]
     // of {logit, expert id} reuse the storage afterwards
     __shared__ __attribute__((aligned(16))) uint8_t smem[RT * 4 * MAX_K * 8];
     static_assert(RT * 4 * MAX_K * 8 >= 2 * RT * 128, "stages fit");
@@ -89,22 +90,22 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     const int t0 = blockIdx.x * RT;
     const int nk = d / 16, nchunks = d / RKC;
 
-    // activation staging by direct-to-LDS copies: wave w, copy j brings rows (4w+j)*8 .. +7 of the chunk;
+    // activation staging by direct-to-LDS copies: wave w, copy j < TS brings rows (TS*w+j)*8 .. +7 of the chunk;
     // lane i -> row i/8, LDS chunk slot i%8, which receives global 16-byte chunk
     // slot ^ (row & 7) ^ ((row >> 3) & 1) (the operand reads then touch all 64 LDS banks evenly)
-    uint32_t xoff[4];
+    uint32_t xoff[TS];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = (wave * 4 + j) * 8 + (lane >> 3);
+    for (int j = 0; j < TS; ++j) {
+        const int row = (wave * TS + j) * 8 + (lane >> 3);
         const int t = min(t0 + row, T - 1);
         xoff[j] = (uint32_t)t * (uint32_t)d * 2u + ((((lane & 7) ^ (row & 7) ^ ((row >> 3) & 1))) << 4);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
     auto issue_x = [&](int kc) {
         const uint8_t* src = reinterpret_cast<const uint8_t*>(x) + (size_t)kc * (RKC * 2);
-        const uint32_t dst = lds0 + (kc & 1) * RT * 128 + wave * 4 * 1024;
+        const uint32_t dst = lds0 + (kc & 1) * RT * 128 + wave * TS * 1024;
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+        for (int j = 0; j < TS; ++j)
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :: "s"(dst + j * 1024), "v"(xoff[j]), "s"(src) : "memory");
     };
@@ -115,11 +116,11 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
 
     // accumulators live in the accumulation registers for the whole K loop; the matrix instructions are
     // volatile asm with a memory clobber, so they and the loads around them stay in source order
-    v16f acc[NS][4];
+    v16f acc[NS][TS];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
 #pragma unroll
-        for (int ts = 0; ts < 4; ++ts)
+        for (int ts = 0; ts < TS; ++ts)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[s][ts][r] = 0.f;
 
@@ -152,9 +153,9 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
         for (int ks = 0; ks < 4; ++ks) {
             const int kk = kc * 4 + ks;
             if (kk + 3 < nk) load_a((ks + 3) & 3, kk + 3);
-            v4i b[4];
+            v4i b[TS];
 #pragma unroll
-            for (int ts = 0; ts < 4; ++ts) {
+            for (int ts = 0; ts < TS; ++ts) {
                 const int row = ts * 32 + l32;
                 b[ts] = *reinterpret_cast<const v4i*>(stage + row * 128 + (((ks * 2 + half) ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
             }
@@ -181,7 +182,7 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
 #pragma unroll
                 for (int p = 0; p < 3; ++p)
 #pragma unroll
-                    for (int ts = 0; ts < 4; ++ts)
+                    for (int ts = 0; ts < TS; ++ts)
                         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
                                      : "+a"(acc[s][ts]) : "v"(a[ks][s][p]), "v"(b[ts]) : "memory");
         }
@@ -196,7 +197,7 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
         for (int i = tid; i < RT * MAX_K; i += 256) sel[i] = 0.f;   // ids outside [0,E) keep logit 0
         __syncthreads();
 #pragma unroll
-        for (int ts = 0; ts < 4; ++ts) {
+        for (int ts = 0; ts < TS; ++ts) {
             const int tok = ts * 32 + l32;
             if (t0 + tok >= T) continue;
             const int32_t* ids = logged_idx + (size_t)(t0 + tok) * k;
@@ -230,9 +231,11 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     // ---- per-wave top-k.  Lane (l32, half) holds, for token ts*32+l32, the logits of experts
     //      wave*32*NS + s*32 + (r/4)*8 + half*4 + (r%4).  Candidates: cand[token][wave][j] = {logit, idx}
     float2* cand = reinterpret_cast<float2*>(smem);
-    uint32_t taken[4] = {0u, 0u, 0u, 0u};                      // bit (s*16 + r)
+    uint32_t taken[TS];                                        // bit (s*16 + r)
 #pragma unroll
-    for (int ts = 0; ts < 4; ++ts) {
+    for (int ts = 0; ts < TS; ++ts) taken[ts] = 0u;
+#pragma unroll
+    for (int ts = 0; ts < TS; ++ts) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
 #pragma unroll
@@ -243,7 +246,7 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     }
     for (int j = 0; j < k; ++j) {
 #pragma unroll
-        for (int ts = 0; ts < 4; ++ts) {
+        for (int ts = 0; ts < TS; ++ts) {
             float bs = 0.f, bl = 0.f;
             int bi = NO_CAND, bpos = 0;
 #pragma unroll
@@ -320,15 +323,24 @@ hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const f
     const int64_t nthreads = (int64_t)E_pad * (D.d / 8);
     hipLaunchKernelGGL(split_router_weights, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, c->stream,
                        W_r, D.E, E_pad, D.d, c->router_planes);
-    const int grid = (D.T + RT - 1) / RT;
-#define MOE_ROUTE_LAUNCH(NS_, IDS_)                                                                             \
-    hipLaunchKernelGGL((route_mfma_kernel<NS_, IDS_>), dim3(grid), dim3(256), 0, c->stream, x, c->router_planes, \
-                       bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w)
+    // token tile: the largest of 128 / 64 / 32 rows that still gives every compute unit a block
+    const int TS = D.T >= 256 * 128 ? 4 : D.T >= 256 * 64 ? 2 : 1;
+    const int grid = (D.T + 32 * TS - 1) / (32 * TS);
+#define MOE_ROUTE_LAUNCH(NS_, TS_, IDS_)                                                                    \
+    hipLaunchKernelGGL((route_mfma_kernel<NS_, TS_, IDS_>), dim3(grid), dim3(256), 0, c->stream, x,         \
+                       c->router_planes, bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w)
+#define MOE_ROUTE_TS(NS_, IDS_)                                                                             \
+    do {                                                                                                    \
+        if (TS == 4) MOE_ROUTE_LAUNCH(NS_, 4, IDS_);                                                        \
+        else if (TS == 2) MOE_ROUTE_LAUNCH(NS_, 2, IDS_);                                                   \
+        else MOE_ROUTE_LAUNCH(NS_, 1, IDS_);                                                                \
+    } while (0)
     if (E_pad == 128) {
-        if (logged_idx) MOE_ROUTE_LAUNCH(1, true); else MOE_ROUTE_LAUNCH(1, false);
+        if (logged_idx) MOE_ROUTE_TS(1, true); else MOE_ROUTE_TS(1, false);
     } else {
-        if (logged_idx) MOE_ROUTE_LAUNCH(2, true); else MOE_ROUTE_LAUNCH(2, false);
+        if (logged_idx) MOE_ROUTE_TS(2, true); else MOE_ROUTE_TS(2, false);
     }
+#undef MOE_ROUTE_TS
 #undef MOE_ROUTE_LAUNCH
     return hipGetLastError();
 }
