@@ -170,6 +170,22 @@ int moe_expert_ffn_fp8_gather(moe_ctx* ctx, const uint8_t* xq_tok, const float* 
 int moe_combine(moe_ctx* ctx, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
                 uint16_t* y_bf16);
 
+/* Length-based load balancing before rollout (paper section 3.1.1): distributes n samples over
+ * n_groups worker groups so that the groups' total predicted generation lengths are about equal.
+ * The paper states the goal only; the rule taken is longest-first list scheduling: samples are
+ * visited by decreasing pred_len (equal lengths by increasing index) and each goes to the group
+ * with the smallest running total that still has room (lowest group index on equal totals).
+ * equal_count != 0: group g takes at most n / n_groups + (g < n % n_groups) samples, i.e. the
+ * batches of synchronous data-parallel workers stay equal-sized; 0: no limit.
+ * Host-side scheduling step: ALL pointers are HOST pointers, no context, no stream, no GPU work.
+ *   pred_len [n] in, >= 0;  group_of [n] out;  order [n] out: sample indices group after group,
+ *   inside a group in the order handed out;  bounds [n_groups+1] out: group g owns
+ *   order[bounds[g] .. bounds[g+1]);  totals [n_groups] out: summed pred_len per group.
+ * MOE_EINVAL on a null pointer (pred_len/group_of/order may be null when n == 0), n < 0,
+ * n_groups < 1 or a negative length; MOE_ENOMEM if temporary host memory cannot be had. */
+int moe_balance_lengths(const int64_t* pred_len, int64_t n, int32_t n_groups, int32_t equal_count,
+                        int32_t* group_of, int64_t* order, int64_t* bounds, int64_t* totals);
+
 /* Device pointers to the hidden activations written by the last
  * moe_expert_ffn_fp8 call (hq [N,F] u8, hs [F/128][N] f32, group-major); valid until the
  * context is destroyed.  For stage-isolated checks. */

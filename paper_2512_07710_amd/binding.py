@@ -20,7 +20,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_route_replay_ids",
            "moe_check_ids", "moe_quantize_fp8", "moe_quantize_weights_fp8", "moe_linear_fp8", "moe_expert_ffn_fp8",
            "moe_expert_ffn_fp8_gather",
-           "moe_combine", "moe_debug_hidden", "moe_profile_enable", "moe_profile_read", "moe_version")
+           "moe_combine", "moe_balance_lengths", "moe_debug_hidden", "moe_profile_enable", "moe_profile_read", "moe_version")
 
 
 class MoEError(RuntimeError):
@@ -58,6 +58,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_expert_ffn_fp8.argtypes = [vp] * 11
     lib.moe_expert_ffn_fp8_gather.argtypes = [vp] * 11
     lib.moe_combine.argtypes = [vp] * 5
+    lib.moe_balance_lengths.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
     lib.moe_debug_hidden.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp)]
     lib.moe_profile_enable.argtypes = [vp, i32]
     lib.moe_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
@@ -166,6 +167,24 @@ def moe_expert_ffn_fp8_gather(ctx, xq_tok, xs_tok, offsets, W1, W3, W2, s1, s3, 
 def moe_combine(ctx, y_perm, inv_perm, topk_w, y) -> None:
     _check(load_library().moe_combine(ctx, _ptr(y_perm, torch.float32), _ptr(inv_perm, torch.int32),
                                       _ptr(topk_w, torch.float32), _ptr(y, torch.bfloat16)), "moe_combine")
+
+
+def moe_balance_lengths(pred_len, n_groups: int, equal_count: bool = True):
+    """Host-side length-based load balancing: pred_len is a CPU int64 tensor [n]; returns CPU tensors
+    (group_of int32 [n], order int64 [n], bounds int64 [n_groups+1], totals int64 [n_groups])."""
+    if pred_len.is_cuda or pred_len.dtype != torch.int64 or not pred_len.is_contiguous() or pred_len.dim() != 1:
+        raise MoEError("expected a contiguous 1-D CPU int64 tensor")
+    if n_groups < 1:
+        raise MoEError("n_groups must be at least 1")
+    n = pred_len.numel()
+    group_of = torch.empty(n, dtype=torch.int32)
+    order = torch.empty(n, dtype=torch.int64)
+    bounds = torch.empty(n_groups + 1, dtype=torch.int64)
+    totals = torch.empty(n_groups, dtype=torch.int64)
+    _check(load_library().moe_balance_lengths(pred_len.data_ptr(), n, n_groups, 1 if equal_count else 0,
+                                              group_of.data_ptr(), order.data_ptr(), bounds.data_ptr(),
+                                              totals.data_ptr()), "moe_balance_lengths")
+    return group_of, order, bounds, totals
 
 
 def moe_debug_hidden(ctx):
