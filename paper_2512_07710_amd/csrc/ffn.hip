@@ -216,18 +216,25 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
 #pragma unroll
         for (int j = 0; j < 4; ++j) dma16(dst + j * 8 * KB, w_off[j], src);
     };
+    auto issue_w1 = [&](int kb, int wslot, int j) {
+        const uint8_t* src = w_base + (size_t)kb * KB;
+        const uint32_t dst = lds_rows + wslot * W_TILE;
+        dma16(dst + j * 8 * KB, w_off[j], src);
+    };
     // 8-row activation copies that lie wholly beyond the expert's last row are not issued at all
     // (a ragged last tile then moves only the rows it has); wave-uniform
     const int x_copies = __builtin_amdgcn_readfirstlane(max(0, min(4, (row_end - wk.row0 - wave * 32 + 7) / 8)));
+    // the skip is a scalar branch inside the asm: the compiler's control flow stays a straight line
+#define X_COPY(KBLK, XSLOT, J)                                                                                  \
+    asm volatile("s_cmp_gt_i32 %3, %4\n\ts_cbranch_scc0 .Lskipx%=\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\t"           \
+                 "global_load_lds_dwordx4 %1, %2\n.Lskipx%=:"                                                   \
+                 :: "s"(lds_rows + X_RING + (XSLOT) * X_TILE + (J) * 8 * KB), "v"(x_off[J]),                    \
+                    "s"(x_base + (size_t)(KBLK) * KB), "s"(x_copies), "n"(J) : "memory", "scc")
     auto issue_x = [&](int kb, int xslot) {
-        const uint8_t* src = x_base + (size_t)kb * KB;
-        const uint32_t dst = lds_rows + X_RING + xslot * X_TILE;
-        // the skip is a scalar branch inside the asm: the compiler's control flow stays a straight line
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            asm volatile("s_cmp_gt_i32 %3, %4\n\ts_cbranch_scc0 .Lskipx%=\n\ts_mov_b32 m0, %0\n\ts_nop 0\n\t"
-                         "global_load_lds_dwordx4 %1, %2\n.Lskipx%=:"
-                         :: "s"(dst + j * 8 * KB), "v"(x_off[j]), "s"(src), "s"(x_copies), "n"(j) : "memory", "scc");
+        X_COPY(kb, xslot, 0);
+        X_COPY(kb, xslot, 1);
+        X_COPY(kb, xslot, 2);
+        X_COPY(kb, xslot, 3);
     };
 
     // ---- weight scales of this wave's rows (wave-uniform -> scalar loads)
@@ -248,10 +255,12 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     // Pipeline.  K block kb of the weight tile lives in ring slot kb % 3, of the activation tile in
     // slot kb % 2.  Each wave passes ONE barrier per K block, placed after its last LDS read of block
     // kb (before sub-tile product 6 of 8).  Behind that barrier block kb+1 is complete in LDS and the
-    // slots of block kb are free: the copies of activation block kb+2 and weight block kb+3 are
-    // issued there (always in that order, so that "all but the newest four copies have landed" is
-    // exactly "everything but the weight block two steps ahead"), and products 6 and 7 already fetch
-    // the first operands of block kb+1 into registers.
+    // slots of block kb are free.  The copies that refill them go out one behind each matrix
+    // instruction (a burst of eight would hold the wave at the issue of the ninth): activation block
+    // kb+2 over products 6 and 7, weight block kb+3 over products 0 and 1 of the next step - always in
+    // that order, so that "all but the newest four copies have landed" is exactly "everything but the
+    // weight block two steps ahead".  Products 6 and 7 already fetch the first operands of block kb+1
+    // into registers.
     issue_x(0, 0);
     issue_w(0, 0);
     if (!wave_active) {
@@ -347,6 +356,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
         int wslot = 0;                                         // ring slot of weight block kb
         for (int kb = 0; kb < nkb; ++kb) {
             const int wnext = (wslot == NW_BUF - 1) ? 0 : wslot + 1;
+            const int wprev = (wslot == 0) ? NW_BUF - 1 : wslot - 1;             // slot of block kb-1 = of block kb+2
             const uint8_t* sW = smem + wslot * W_TILE + a_row;                   // block kb
             const uint8_t* sWn = smem + wnext * W_TILE + a_row;                  // block kb+1
             const uint8_t* sXn = smem + b_row + ((kb & 1) ^ 1) * X_TILE;         // block kb+1
@@ -369,6 +379,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                     for (int t2 = 0; t2 < 2; ++t2) asm volatile("v_mov_b32 %0, %1" : "=v"(xs_cur[t2]) : "v"(xs_n[t2]));
                 }
                 if (ts == 0) mfma_first(T0, a[s & 1][0], b[0][0]); else mfma_first(T1, a[s & 1][0], b[1][0]);
+                // one copy behind every matrix instruction: weight block kb+2 over products 0 and 1
+                if (i < 2 && kb >= 1 && kb + 2 < nkb) issue_w1(kb + 2, wprev, i * 2);
+                if (i == 7 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 2);
                 if (ts == 0 && s < 3) {
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
@@ -380,11 +393,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                     if (kb + 2 < nkb) {
                         xs_load(xs_n[0], kb + 2, 0);
                         xs_load(xs_n[1], kb + 2, 1);
-                        issue_x(kb + 2, kb & 1);
+                        X_COPY(kb + 2, kb & 1, 0);
                     }
                 }
-                if (i == 7 && kb + 3 < nkb) issue_w(kb + 3, wslot);
                 if (ts == 0) mfma_acc(T0, a[s & 1][1], b[0][1]); else mfma_acc(T1, a[s & 1][1], b[1][1]);
+                if (i < 2 && kb >= 1 && kb + 2 < nkb) issue_w1(kb + 2, wprev, i * 2 + 1);
+                if (i == 6 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 1);
+                if (i == 7 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 3);
                 if (i == 0) {
                     FOLD(3, 1, sc_pend);
                 } else {
@@ -412,6 +427,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
         asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
         FOLD(3, 1, sc_pend);
 #undef FOLD
+#undef X_COPY
     }
     asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();                              // every wave is done with the operand rings

@@ -196,6 +196,12 @@ def test_small_ragged_shapes(gpu_lib, seed):
     _run_and_check_layer(gpu_lib, cfg, "routed")
 
 
+def test_single_k_block_in_both_gemms(gpu_lib):
+    """d = F = 128: each GEMM's K loop has exactly one block (prologue and drain only), output tiles half empty."""
+    _run_and_check_layer(gpu_lib, MoEConfig("tiny", T=400, d=128, E=4, k=2, F=128, modes=("routed",), seed=21), "routed")
+    _run_and_check_layer(gpu_lib, MoEConfig("tiny3", T=300, d=384, E=3, k=1, F=384, modes=("routed",), seed=22), "routed")
+
+
 def test_k_equals_e_and_single_expert(gpu_lib):
     _run_and_check_layer(gpu_lib, MoEConfig("dense", T=130, d=256, E=4, k=4, F=256, modes=("routed",), seed=5), "routed")
     _run_and_check_layer(gpu_lib, MoEConfig("one", T=200, d=128, E=1, k=1, F=384, modes=("routed",), seed=6), "routed")
