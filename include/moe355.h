@@ -22,6 +22,9 @@
  *     (OCP "FN" variant: bias 7, max 448, no infinities, 0x7F/0xFF = NaN).
  *   - Return value: 0 on success, a negative MOE_E* code otherwise.  On an error
  *     detected by argument validation nothing has been enqueued.
+ *   - An empty batch is legal: with T == 0 (or rows == 0 for the calls that take a row
+ *     count) the arrays that would have no elements may be null; the routing calls then
+ *     only write offsets[0..E] = 0 and the other calls enqueue nothing.
  */
 #ifndef MOE355_H
 #define MOE355_H

@@ -9,6 +9,12 @@ namespace {
 
 inline int hip_rc(hipError_t e) { return e == hipSuccess ? MOE_OK : MOE_EHIP; }
 
+// T == 0: the per-token arrays have no elements and may be null; offsets is all zeros
+int route_empty(moe_ctx* c, int32_t* offsets) {
+    if (!offsets) return MOE_EINVAL;
+    return hip_rc(hipMemsetAsync(offsets, 0, sizeof(int32_t) * (size_t)(c->dims.E + 1), c->stream));
+}
+
 bool dims_ok(const moe_dims* d) {
     if (!d) return false;
     if (d->T < 0 || d->d <= 0 || d->F <= 0 || d->E <= 0 || d->k <= 0) return false;
@@ -93,8 +99,9 @@ int moe_destroy(moe_ctx* c) {
 
 int moe_route(moe_ctx* c, const uint16_t* x, const float* W_r, const float* bias, int32_t k,
               int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm, int32_t* inv_perm) {
-    if (!c || !x || !W_r || !topk_idx || !topk_w || !offsets || !perm || !inv_perm) return MOE_EINVAL;
-    if (k != c->dims.k) return MOE_EINVAL;
+    if (!c || k != c->dims.k) return MOE_EINVAL;
+    if (c->dims.T == 0) return route_empty(c, offsets);
+    if (!x || !W_r || !topk_idx || !topk_w || !offsets || !perm || !inv_perm) return MOE_EINVAL;
     hipError_t e = launch_route(c, x, W_r, bias, nullptr, topk_idx, topk_w);
     if (e != hipSuccess) return MOE_EHIP;
     return hip_rc(launch_permute(c, topk_idx, nullptr, nullptr, nullptr, offsets, perm, inv_perm));
@@ -104,8 +111,9 @@ int moe_route_replay(moe_ctx* c, const uint16_t* x, const int32_t* logged_idx, c
                      int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm,
                      int32_t* inv_perm) {
     (void)x;
-    if (!c || !logged_idx || !logged_w || !topk_idx || !topk_w || !offsets || !perm || !inv_perm)
-        return MOE_EINVAL;
+    if (!c) return MOE_EINVAL;
+    if (c->dims.T == 0) return route_empty(c, offsets);
+    if (!logged_idx || !logged_w || !topk_idx || !topk_w || !offsets || !perm || !inv_perm) return MOE_EINVAL;
     int32_t* idx_copy = (topk_idx == logged_idx) ? nullptr : topk_idx;
     float* w_copy = (topk_w == logged_w) ? nullptr : topk_w;
     return hip_rc(launch_permute(c, logged_idx, idx_copy, logged_w, w_copy, offsets, perm, inv_perm));
@@ -113,7 +121,9 @@ int moe_route_replay(moe_ctx* c, const uint16_t* x, const int32_t* logged_idx, c
 
 int moe_route_replay_ids(moe_ctx* c, const uint16_t* x, const float* W_r, const int32_t* logged_idx,
                          int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm, int32_t* inv_perm) {
-    if (!c || !x || !W_r || !logged_idx || !topk_idx || !topk_w || !offsets || !perm || !inv_perm) return MOE_EINVAL;
+    if (!c) return MOE_EINVAL;
+    if (c->dims.T == 0) return route_empty(c, offsets);
+    if (!x || !W_r || !logged_idx || !topk_idx || !topk_w || !offsets || !perm || !inv_perm) return MOE_EINVAL;
     hipError_t e = launch_route(c, x, W_r, nullptr, logged_idx, topk_idx, topk_w);
     if (e != hipSuccess) return MOE_EHIP;
     return hip_rc(launch_permute(c, topk_idx, nullptr, nullptr, nullptr, offsets, perm, inv_perm));
@@ -133,11 +143,12 @@ int moe_check_ids(moe_ctx* c) {
 
 int moe_quantize_fp8(moe_ctx* c, const uint16_t* x, int64_t rows_in, int32_t cols, int32_t block,
                      const int32_t* dst_rows, int32_t fanout, uint8_t* q, float* scales) {
-    if (!c || !x || !q || !scales) return MOE_EINVAL;
+    if (!c) return MOE_EINVAL;
     if (block != QBLOCK || cols <= 0 || cols % QBLOCK || rows_in < 0 || fanout < 1) return MOE_EINVAL;
     if (!dst_rows && fanout != 1) return MOE_EINVAL;
     if (rows_in * (int64_t)fanout > (int64_t)1 << 30) return MOE_EINVAL;
     if (rows_in == 0) return MOE_OK;
+    if (!x || !q || !scales) return MOE_EINVAL;
     return hip_rc(launch_quantize(c->stream, x, rows_in, cols, dst_rows, fanout, q, scales));
 }
 
@@ -162,23 +173,26 @@ int moe_linear_fp8(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t rows,
 int moe_expert_ffn_fp8(moe_ctx* c, const uint8_t* xq, const float* xs, const int32_t* offsets,
                        const uint8_t* W1, const uint8_t* W3, const uint8_t* W2, const float* s1,
                        const float* s3, const float* s2, float* y_perm) {
-    if (!c || !xq || !xs || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
+    if (!c) return MOE_EINVAL;
     if (c->dims.T == 0) return MOE_OK;
+    if (!xq || !xs || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
     return hip_rc(launch_expert_ffn(c, xq, xs, false, offsets, W1, W3, W2, s1, s3, s2, y_perm));
 }
 
 int moe_expert_ffn_fp8_gather(moe_ctx* c, const uint8_t* xq_tok, const float* xs_tok, const int32_t* offsets,
                               const uint8_t* W1, const uint8_t* W3, const uint8_t* W2, const float* s1,
                               const float* s3, const float* s2, float* y_perm) {
-    if (!c || !xq_tok || !xs_tok || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
+    if (!c) return MOE_EINVAL;
     if (c->dims.T == 0) return MOE_OK;
+    if (!xq_tok || !xs_tok || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
     return hip_rc(launch_expert_ffn(c, xq_tok, xs_tok, true, offsets, W1, W3, W2, s1, s3, s2, y_perm));
 }
 
 int moe_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
                 uint16_t* y) {
-    if (!c || !y_perm || !inv_perm || !topk_w || !y) return MOE_EINVAL;
+    if (!c) return MOE_EINVAL;
     if (c->dims.T == 0) return MOE_OK;
+    if (!y_perm || !inv_perm || !topk_w || !y) return MOE_EINVAL;
     return hip_rc(launch_combine(c, y_perm, inv_perm, topk_w, y));
 }
 

@@ -1,0 +1,83 @@
+"""GPU parity at the edges: the library's maximum expert count and fan-out, degenerate routings (every token
+to one expert, k = 1), and the empty batch."""
+import numpy as np
+import pytest
+import torch
+
+from workloads import MoEConfig
+from test_gpu_parity import _run_and_check_layer
+
+pytestmark = pytest.mark.gpu
+
+
+def test_maximum_experts_and_fanout(gpu_lib):
+    """E = 256 and k = 16 are the library's limits; most experts get a handful of rows."""
+    _run_and_check_layer(gpu_lib, MoEConfig("max", T=70, d=256, E=256, k=16, F=128, modes=("routed",), seed=31), "routed")
+    _run_and_check_layer(gpu_lib, MoEConfig("maxk", T=50, d=128, E=16, k=16, F=256, modes=("routed",), seed=32), "routed")
+
+
+def test_every_token_to_the_same_experts(gpu_lib):
+    """Replay logs that send all tokens to one expert (k = 1, weight 1) or to the same pair: every other expert
+    is empty and the busy ones span several row tiles with a ragged last one."""
+    cfg = MoEConfig("one_hot", T=700, d=256, E=8, k=1, F=256, modes=("replay",), seed=33)
+    ids = np.full((cfg.T, 1), 5, dtype=np.int32)
+    w = np.ones((cfg.T, 1), dtype=np.float32)
+    _run_and_check_layer(gpu_lib, cfg, "replay", log=(ids, w))
+    cfg = MoEConfig("pair", T=530, d=128, E=6, k=2, F=384, modes=("replay",), seed=34)
+    ids = np.tile(np.array([[4, 1]], dtype=np.int32), (cfg.T, 1))
+    rng = np.random.default_rng(34)
+    w = rng.dirichlet(np.ones(2), cfg.T).astype(np.float32)
+    _run_and_check_layer(gpu_lib, cfg, "replay", log=(ids, w))
+
+
+def test_k1_routed_weight_is_exactly_one(gpu_lib):
+    cfg = MoEConfig("k1", T=300, d=256, E=12, k=1, F=128, modes=("routed",), seed=35)
+    _run_and_check_layer(gpu_lib, cfg, "routed")
+    from workloads import make_inputs
+    inp = make_inputs(cfg, with_experts=False)
+    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+    try:
+        layer.route(inp["x"].cuda(), inp["W_r"].cuda(), None)
+        assert torch.all(layer.topk_w == 1.0)
+    finally:
+        layer.close()
+
+
+def test_empty_batch(gpu_lib):
+    """T = 0: every call succeeds, nothing is launched, offsets come back as zeros."""
+    E, d, F, k = 8, 256, 128, 2
+    ctx = gpu_lib.moe_create(0, d, E, k, F)
+    try:
+        dev = "cuda"
+        x = torch.empty((0, d), dtype=torch.bfloat16, device=dev)
+        W_r = torch.randn((E, d), dtype=torch.float32, device=dev)
+        idx = torch.empty((0, k), dtype=torch.int32, device=dev)
+        w = torch.empty((0, k), dtype=torch.float32, device=dev)
+        perm = torch.empty(0, dtype=torch.int32, device=dev)
+        inv = torch.empty(0, dtype=torch.int32, device=dev)
+        for call in ("route", "replay", "replay_ids"):
+            offsets = torch.full((E + 1,), 7, dtype=torch.int32, device=dev)
+            if call == "route":
+                gpu_lib.moe_route(ctx, x, W_r, None, k, idx, w, offsets, perm, inv)
+            elif call == "replay":
+                gpu_lib.moe_route_replay(ctx, x, idx, w, idx, w, offsets, perm, inv)
+            else:
+                gpu_lib.moe_route_replay_ids(ctx, x, W_r, idx, idx, w, offsets, perm, inv)
+            torch.cuda.synchronize()
+            assert torch.all(offsets == 0)
+        assert gpu_lib.moe_check_ids(ctx) == 0
+        xq = torch.empty((0, d), dtype=torch.uint8, device=dev)
+        xs = torch.empty((d // 128, 0), dtype=torch.float32, device=dev)
+        gpu_lib.moe_quantize_fp8(ctx, x, 0, d, 128, None, 1, xq, xs)
+        W = torch.zeros((E, F, d), dtype=torch.uint8, device=dev)
+        W2 = torch.zeros((E, d, F), dtype=torch.uint8, device=dev)
+        s13 = torch.ones((E, F // 128, d // 128), dtype=torch.float32, device=dev)
+        s2 = torch.ones((E, d // 128, F // 128), dtype=torch.float32, device=dev)
+        y_perm = torch.empty((0, d), dtype=torch.float32, device=dev)
+        gpu_lib.moe_expert_ffn_fp8(ctx, xq, xs, offsets, W, W, W2, s13, s13, s2, y_perm)
+        gpu_lib.moe_expert_ffn_fp8_gather(ctx, xq, xs, offsets, W, W, W2, s13, s13, s2, y_perm)
+        y = torch.empty((0, d), dtype=torch.bfloat16, device=dev)
+        gpu_lib.moe_combine(ctx, y_perm, inv, w, y)
+        torch.cuda.synchronize()
+    finally:
+        gpu_lib.moe_destroy(ctx)

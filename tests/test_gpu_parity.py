@@ -76,8 +76,9 @@ def _check_permutation(idx, E, layer):
     return offsets, perm, inv_perm
 
 
-def _run_and_check_layer(gpu_lib, cfg: MoEConfig, mode: str, seed=None):
-    """Full layer at `cfg` (must be small enough for the whole oracle)."""
+def _run_and_check_layer(gpu_lib, cfg: MoEConfig, mode: str, seed=None, log=None):
+    """Full layer at `cfg` (must be small enough for the whole oracle).  log = (ids, weights) replaces the
+    replay log that would otherwise be the oracle's own routing."""
     inp = make_inputs(cfg, seed=seed)
     h, dv = _host(inp), _dev(inp)
     layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
@@ -88,7 +89,9 @@ def _run_and_check_layer(gpu_lib, cfg: MoEConfig, mode: str, seed=None):
             torch.cuda.synchronize()
             _compare_routing(h, layer, bias_h)
         else:
-            if cfg.log == "zipf":
+            if log is not None:
+                log_idx, log_w = log
+            elif cfg.log == "zipf":
                 log_idx, log_w = h["logged_idx"], h["logged_w"]
             else:
                 log_idx, log_w, _ = om.route(h["x"], h["W_r"], cfg.k, bias_h)
