@@ -481,25 +481,40 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
             }
         }
     } else {
+        // The accumulators hold 16-byte pieces of 64 different rows per store instruction, which the memory
+        // pipeline would take as 64 separate requests.  Each wave therefore turns its 128 x 64 block through a
+        // private LDS region (the operand rings are free now), 64 features at a time, and writes 256 contiguous
+        // bytes of a row with every 16 lanes.
         if (wave_active) {
+            constexpr int TS_STRIDE = 68;                      // floats per staged token row: 64 + 4 of padding
+            float* const stage = reinterpret_cast<float*>(smem) + wave * (64 * TS_STRIDE);
 #pragma unroll
-            for (int ts = 0; ts < 2; ++ts) {
-                const int p = wk.row0 + wt * 64 + ts * 32 + l32;
-                if (p < row_end) {
+            for (int hh = 0; hh < 2; ++hh) {
 #pragma unroll
-                    for (int s = 0; s < 4; ++s) {
-                        const int fbase = f0 + wf * 128 + s * 32 + half * 4;
-                        if (fbase < NOUT) {
-                            float* dst = y_perm + (size_t)p * NOUT + fbase;
+                for (int ts = 0; ts < 2; ++ts)
 #pragma unroll
-                            for (int r4 = 0; r4 < 4; ++r4) {
-                                const float4 v = make_float4(acc[s][ts][r4 * 4], acc[s][ts][r4 * 4 + 1],
-                                                             acc[s][ts][r4 * 4 + 2], acc[s][ts][r4 * 4 + 3]);
-                                *reinterpret_cast<float4*>(dst + r4 * 8) = v;
-                            }
+                    for (int sl = 0; sl < 2; ++sl)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const int s = hh * 2 + sl;
+                            const float4 v = make_float4(acc[s][ts][r4 * 4], acc[s][ts][r4 * 4 + 1],
+                                                         acc[s][ts][r4 * 4 + 2], acc[s][ts][r4 * 4 + 3]);
+                            *reinterpret_cast<float4*>(stage + (ts * 32 + l32) * TS_STRIDE + sl * 32 + r4 * 8 + half * 4) = v;
                         }
+                // the lanes of a wave run in step: once its own LDS writes have completed, every lane's have
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                const int fcol = f0 + wf * 128 + hh * 64;
+                if (fcol < NOUT) {
+#pragma unroll 4
+                    for (int it = 0; it < 16; ++it) {
+                        const int trow = it * 4 + (lane >> 4);
+                        const float4 v = *reinterpret_cast<const float4*>(stage + trow * TS_STRIDE + (lane & 15) * 4);
+                        const int p = wk.row0 + wt * 64 + trow;
+                        if (p < row_end)
+                            *reinterpret_cast<float4*>(y_perm + (size_t)p * NOUT + fcol + (lane & 15) * 4) = v;
                     }
                 }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // all reads done before the region is rewritten
             }
         }
     }
