@@ -214,6 +214,22 @@ def main() -> int:
         ext["dense_linear_ms"] = t_lin
         ext["dense_linear_tflops"] = 2.0 * rows_l * d * rows_w / (t_lin * 1e-3) / 1e12
         ext["dense_linear_shape"] = [rows_l, d, rows_w]
+    # the same layer with the expert outputs kept as 16-bit block-scaled rows between the down GEMM and the combine
+    # (half the bytes of that round trip; the headline above keeps fp32 rows)
+    i16 = {}
+    if "routed" in cfg.modes:
+        i16["routed_ms_per_step"] = timed(lambda: layer.forward_routed(x, W_r, bias, inp, fused="i16"))[0]
+    ms_i16, _, g2_i16, _ = timed(lambda: layer.forward_replay(x, log_idx, log_w, inp, fused="i16"))
+    i16["replay_ms_per_step"] = ms_i16
+    i16["gemm2_ms"] = g2_i16
+    i16["combine_ms"] = stage_ms(layer.combine_i16)
+    ci_bytes = 2.0 * N * d + 4.0 * N * d / 128 + 8.0 * N + 2.0 * T * d
+    i16["combine_GBs"] = ci_bytes / (i16["combine_ms"] * 1e-3) / 1e9
+    i16["combine_frac_hbm"] = i16["combine_GBs"] / HBM_PEAK_GBS
+    head_i16 = i16.get("routed_ms_per_step", ms_i16) if head_mode == "routed" else ms_i16
+    i16["tflops"] = flop / (head_i16 * 1e-3) / 1e12
+    i16["tokens_per_s"] = T / (head_i16 * 1e-3)
+    ext["i16_expert_outputs"] = i16
     out["extensions"] = ext
     del w_bf16, wq, wsc
     if not args.no_cpu_baseline:

@@ -173,6 +173,24 @@ int moe_expert_ffn_fp8_gather(moe_ctx* ctx, const uint8_t* xq_tok, const float* 
 int moe_combine(moe_ctx* ctx, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
                 uint16_t* y_bf16);
 
+/* 16-bit storage of the expert outputs between the down projection and the combine (an
+ * implementation format of this library; the paper does not fix the precision of that
+ * intermediate, fp32 y_perm above is the reference form).  Same computation as
+ * moe_expert_ffn_fp8_gather, but row p of the result leaves as
+ *   ys[p, g] = amax_g / 32767 with amax_g = max |y_perm[p, 128g .. 128g+127]|   (1 if all zero), fp32,
+ *   yq[p, c] = round-half-even(y_perm[p, c] * (32767 / amax_g)) as int16, product and quotient in fp32,
+ * yq [N, d] and ys [N, d/128] row-major, device pointers owned by the caller: half the bytes of
+ * fp32 rows for a relative error of about 2^-16 of each group's maximum, far inside the layer's
+ * 2e-3 budget.  moe_combine_i16 is moe_combine over such rows:
+ *   y[t, c] = bf16( sum_j (topk_w[t, j] * ys[r_j, c/128]) * yq[r_j, c] ),  r_j = inv_perm[t*k + j],
+ * fp32 multiply-adds in slot order.  Errors as for the fp32 calls. */
+int moe_expert_ffn_fp8_gather_i16(moe_ctx* ctx, const uint8_t* xq_tok, const float* xs_tok,
+                                  const int32_t* offsets, const uint8_t* W1, const uint8_t* W3,
+                                  const uint8_t* W2, const float* s1, const float* s3, const float* s2,
+                                  int16_t* yq, float* ys);
+int moe_combine_i16(moe_ctx* ctx, const int16_t* yq, const float* ys, const int32_t* inv_perm,
+                    const float* topk_w, uint16_t* y_bf16);
+
 /* Length-based load balancing before rollout (paper section 3.1.1): distributes n samples over
  * n_groups worker groups so that the groups' total predicted generation lengths are about equal.
  * The paper states the goal only; the rule taken is longest-first list scheduling: samples are

@@ -154,15 +154,19 @@ def quantize_rows_i16(y: np.ndarray):
     intermediate; plain fp32 is the reference form).
 
     y [R,C] float64 holding fp32-representable values, C a multiple of 128.  Per row and 128 contiguous
-    columns: s = fp32(amax/32767) (1 if the group is all zero), code = round-half-even(fp32(y/s)) as int16.
-    Returns codes i16 [R,C] and scales f32 [R, C/128].  |y - s*code| <= s/2 up to fp32 rounding of y/s.
+    columns: s = fp32(amax/32767) is the stored scale and q = fp32(32767/amax) the multiplier (both 1 if the
+    group is all zero); code = round-half-even(fp32(y*q)) as int16.  (A multiplier, not a division by s: the
+    format is this library's own, and one reciprocal per group keeps the kernel's epilogue short.)
+    Returns codes i16 [R,C] and scales f32 [R, C/128].  |y - s*code| <= s/2 up to a few fp32 roundings.
     """
     R, C = y.shape
     assert C % G == 0
     yg = y.reshape(R, C // G, G)
     amax = np.abs(yg).max(axis=2)
+    safe = np.where(amax == 0, 1.0, amax)
     s = np.where(amax == 0, 1.0, amax / 32767.0).astype(np.float32)
-    r = (yg / s.astype(np.float64)[:, :, None]).astype(np.float32)
+    q = np.where(amax == 0, 1.0, 32767.0 / safe).astype(np.float32)
+    r = (yg * q.astype(np.float64)[:, :, None]).astype(np.float32)
     codes = np.rint(r.astype(np.float64)).astype(np.int16)      # numpy's rint rounds half to even
     return codes.reshape(R, C), s
 

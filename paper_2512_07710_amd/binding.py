@@ -20,7 +20,7 @@ _lib: Optional[ctypes.CDLL] = None
 EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_route_replay_ids",
            "moe_check_ids", "moe_quantize_fp8", "moe_quantize_weights_fp8", "moe_linear_fp8", "moe_expert_ffn_fp8",
            "moe_expert_ffn_fp8_gather",
-           "moe_combine", "moe_balance_lengths", "moe_debug_hidden", "moe_profile_enable", "moe_profile_read", "moe_version")
+           "moe_expert_ffn_fp8_gather_i16", "moe_combine", "moe_combine_i16", "moe_balance_lengths", "moe_debug_hidden", "moe_profile_enable", "moe_profile_read", "moe_version")
 
 
 class MoEError(RuntimeError):
@@ -57,7 +57,9 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_quantize_fp8.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp]
     lib.moe_expert_ffn_fp8.argtypes = [vp] * 11
     lib.moe_expert_ffn_fp8_gather.argtypes = [vp] * 11
+    lib.moe_expert_ffn_fp8_gather_i16.argtypes = [vp] * 12
     lib.moe_combine.argtypes = [vp] * 5
+    lib.moe_combine_i16.argtypes = [vp] * 6
     lib.moe_balance_lengths.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
     lib.moe_debug_hidden.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp)]
     lib.moe_profile_enable.argtypes = [vp, i32]
@@ -162,6 +164,21 @@ def moe_expert_ffn_fp8_gather(ctx, xq_tok, xs_tok, offsets, W1, W3, W2, s1, s3, 
                                                     _ptr(offsets, torch.int32), _ptr(W1, u8), _ptr(W3, u8),
                                                     _ptr(W2, u8), _ptr(s1, f32), _ptr(s3, f32), _ptr(s2, f32),
                                                     _ptr(y_perm, f32)), "moe_expert_ffn_fp8_gather")
+
+
+def moe_expert_ffn_fp8_gather_i16(ctx, xq_tok, xs_tok, offsets, W1, W3, W2, s1, s3, s2, yq, ys) -> None:
+    u8, f32 = torch.uint8, torch.float32
+    _check(load_library().moe_expert_ffn_fp8_gather_i16(ctx, _ptr(xq_tok, u8), _ptr(xs_tok, f32),
+                                                        _ptr(offsets, torch.int32), _ptr(W1, u8), _ptr(W3, u8),
+                                                        _ptr(W2, u8), _ptr(s1, f32), _ptr(s3, f32), _ptr(s2, f32),
+                                                        _ptr(yq, torch.int16), _ptr(ys, f32)),
+           "moe_expert_ffn_fp8_gather_i16")
+
+
+def moe_combine_i16(ctx, yq, ys, inv_perm, topk_w, y) -> None:
+    _check(load_library().moe_combine_i16(ctx, _ptr(yq, torch.int16), _ptr(ys, torch.float32),
+                                          _ptr(inv_perm, torch.int32), _ptr(topk_w, torch.float32),
+                                          _ptr(y, torch.bfloat16)), "moe_combine_i16")
 
 
 def moe_combine(ctx, y_perm, inv_perm, topk_w, y) -> None:

@@ -146,7 +146,9 @@ __device__ inline uint32_t pack4_e4m3(float a, float b, float c, float d) {
 // row_token[p]: the expert-ordered copy of the codes is never materialised.  The scales act_s
 // [K/128][n_rows] are in sorted order in both cases (they are 1/128 of the data; a lane-scattered
 // scale read per K step would cost more than it saves).
-template <bool GATED, bool GATHER>
+// Q16 (down projection only): the output goes out as 16-bit codes with one fp32 scale per row and 128 columns
+// (s = amax / 32767, code = round(y * (32767 / amax))), through the hq / hs arguments, instead of fp32 rows.
+template <bool GATED, bool GATHER, bool Q16 = false>
 __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restrict__ act,
                                                         const float* __restrict__ act_s, int n_rows,
                                                         const int32_t* __restrict__ row_token,
@@ -485,7 +487,50 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
         // pipeline would take as 64 separate requests.  Each wave therefore turns its 128 x 64 block through a
         // private LDS region (the operand rings are free now), 64 features at a time, and writes 256 contiguous
         // bytes of a row with every 16 lanes.
-        if (wave_active) {
+        if (Q16) {
+            // Same turn through LDS with 16-bit codes: the wave's 128 features are exactly one scale group, whose
+            // amax is a lane-local maximum and one exchange between the two lanes that share a token.
+            if (wave_active && f0 + wf * 128 < NOUT) {
+                constexpr int Q_STRIDE = 272;                  // bytes per staged token row: 128 codes + 16 of padding
+                uint8_t* const stage = smem + wave * (64 * Q_STRIDE);
+                int16_t* const yq = reinterpret_cast<int16_t*>(hq);
+                const int blk = (f0 + wf * 128) / QBLOCK;
+#pragma unroll
+                for (int ts = 0; ts < 2; ++ts) {
+                    float am = 0.f;
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) am = fmaxf(am, fabsf(acc[s][ts][r]));
+                    am = fmaxf(am, __shfl_xor(am, 32));
+                    const float sc = (am == 0.f) ? 1.0f : am / 32767.0f;      // stored scale
+                    const float mul = (am == 0.f) ? 1.0f : 32767.0f / am;     // the format's multiplier: one division per group
+                    uint8_t* srow = stage + (ts * 32 + l32) * Q_STRIDE + half * 8;
+#pragma unroll
+                    for (int s = 0; s < 4; ++s)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const int c0 = (int)rintf(acc[s][ts][r4 * 4] * mul), c1 = (int)rintf(acc[s][ts][r4 * 4 + 1] * mul);
+                            const int c2 = (int)rintf(acc[s][ts][r4 * 4 + 2] * mul), c3 = (int)rintf(acc[s][ts][r4 * 4 + 3] * mul);
+                            uint2 v;
+                            v.x = ((uint32_t)c0 & 0xFFFFu) | ((uint32_t)c1 << 16);
+                            v.y = ((uint32_t)c2 & 0xFFFFu) | ((uint32_t)c3 << 16);
+                            *reinterpret_cast<uint2*>(srow + (s * 32 + r4 * 8) * 2) = v;
+                        }
+                    const int p = wk.row0 + wt * 64 + ts * 32 + l32;
+                    if (p < row_end && half == 0) hs[(size_t)p * nblk_out + blk] = sc;
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll 4
+                for (int it = 0; it < 16; ++it) {
+                    const int trow = it * 4 + (lane >> 4);
+                    const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * Q_STRIDE + (lane & 15) * 16);
+                    const int p = wk.row0 + wt * 64 + trow;
+                    if (p < row_end)
+                        *reinterpret_cast<uint4*>(yq + (size_t)p * NOUT + f0 + wf * 128 + (lane & 15) * 8) = v;
+                }
+            }
+        } else if (wave_active) {
             constexpr int TS_STRIDE = 68;                      // floats per staged token row: 64 + 4 of padding
             float* const stage = reinterpret_cast<float*>(smem) + wave * (64 * TS_STRIDE);
 #pragma unroll
@@ -531,9 +576,10 @@ size_t ffn_work_bytes(int max_tiles, int F, int d) {
 static hipError_t set_lds_limits() {
     static bool attr_set = false;
     if (attr_set) return hipSuccess;
-    const void* kernels[3] = {reinterpret_cast<const void*>(&ffn_gemm<true, false>),
+    const void* kernels[4] = {reinterpret_cast<const void*>(&ffn_gemm<true, false>),
                               reinterpret_cast<const void*>(&ffn_gemm<true, true>),
-                              reinterpret_cast<const void*>(&ffn_gemm<false, false>)};
+                              reinterpret_cast<const void*>(&ffn_gemm<false, false>),
+                              reinterpret_cast<const void*>(&ffn_gemm<false, false, true>)};
     for (const void* k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
         if (e != hipSuccess) return e;
@@ -554,9 +600,10 @@ __global__ __launch_bounds__(256) void gather_scales(const float* __restrict__ i
 // gathered == false: xq/xs are the expert-ordered activations [N,d], [d/128][N].
 // gathered == true : xq/xs are in token order [T,d], [d/128][T]; sorted row p reads token c->row_token[p]
 //                    (the scales are first brought into sorted order in the context's workspace).
+// yq != nullptr    : the down projection writes 16-bit codes yq [N,d] and scales ys [N][d/128] instead of y_perm.
 hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, bool gathered, const int32_t* offsets,
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2, const float* s1,
-                             const float* s3, const float* s2, float* y_perm) {
+                             const float* s3, const float* s2, float* y_perm, int16_t* yq, float* ys) {
     const moe_dims& D = c->dims;
     hipError_t ea = set_lds_limits();
     if (ea != hipSuccess) return ea;
@@ -586,9 +633,16 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, boo
     }
     if (ev) (void)hipEventRecord(ev[1], c->stream);
     const int grid2 = ((c->max_tiles * nft2 + NXCD - 1) / NXCD) * NXCD;
-    hipLaunchKernelGGL((ffn_gemm<false, false>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq, c->hs, N,
-                       (const int32_t*)nullptr, offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2,
-                       (const float*)nullptr, D.F, D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
+    if (yq) {
+        // 16-bit output: codes and scales travel through the kernel's hq / hs arguments
+        hipLaunchKernelGGL((ffn_gemm<false, false, true>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq,
+                           c->hs, N, (const int32_t*)nullptr, offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2,
+                           (const float*)nullptr, D.F, D.d, reinterpret_cast<uint8_t*>(yq), ys, (float*)nullptr);
+    } else {
+        hipLaunchKernelGGL((ffn_gemm<false, false>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq, c->hs,
+                           N, (const int32_t*)nullptr, offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2,
+                           (const float*)nullptr, D.F, D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
+    }
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     return hipGetLastError();
 }

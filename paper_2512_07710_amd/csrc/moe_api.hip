@@ -176,7 +176,7 @@ int moe_expert_ffn_fp8(moe_ctx* c, const uint8_t* xq, const float* xs, const int
     if (!c) return MOE_EINVAL;
     if (c->dims.T == 0) return MOE_OK;
     if (!xq || !xs || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
-    return hip_rc(launch_expert_ffn(c, xq, xs, false, offsets, W1, W3, W2, s1, s3, s2, y_perm));
+    return hip_rc(launch_expert_ffn(c, xq, xs, false, offsets, W1, W3, W2, s1, s3, s2, y_perm, nullptr, nullptr));
 }
 
 int moe_expert_ffn_fp8_gather(moe_ctx* c, const uint8_t* xq_tok, const float* xs_tok, const int32_t* offsets,
@@ -185,7 +185,24 @@ int moe_expert_ffn_fp8_gather(moe_ctx* c, const uint8_t* xq_tok, const float* xs
     if (!c) return MOE_EINVAL;
     if (c->dims.T == 0) return MOE_OK;
     if (!xq_tok || !xs_tok || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !y_perm) return MOE_EINVAL;
-    return hip_rc(launch_expert_ffn(c, xq_tok, xs_tok, true, offsets, W1, W3, W2, s1, s3, s2, y_perm));
+    return hip_rc(launch_expert_ffn(c, xq_tok, xs_tok, true, offsets, W1, W3, W2, s1, s3, s2, y_perm, nullptr, nullptr));
+}
+
+int moe_expert_ffn_fp8_gather_i16(moe_ctx* c, const uint8_t* xq_tok, const float* xs_tok, const int32_t* offsets,
+                                  const uint8_t* W1, const uint8_t* W3, const uint8_t* W2, const float* s1,
+                                  const float* s3, const float* s2, int16_t* yq, float* ys) {
+    if (!c) return MOE_EINVAL;
+    if (c->dims.T == 0) return MOE_OK;
+    if (!xq_tok || !xs_tok || !offsets || !W1 || !W3 || !W2 || !s1 || !s3 || !s2 || !yq || !ys) return MOE_EINVAL;
+    return hip_rc(launch_expert_ffn(c, xq_tok, xs_tok, true, offsets, W1, W3, W2, s1, s3, s2, nullptr, yq, ys));
+}
+
+int moe_combine_i16(moe_ctx* c, const int16_t* yq, const float* ys, const int32_t* inv_perm, const float* topk_w,
+                    uint16_t* y) {
+    if (!c) return MOE_EINVAL;
+    if (c->dims.T == 0) return MOE_OK;
+    if (!yq || !ys || !inv_perm || !topk_w || !y) return MOE_EINVAL;
+    return hip_rc(launch_combine_i16(c, yq, ys, inv_perm, topk_w, y));
 }
 
 int moe_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm, const float* topk_w,

@@ -48,7 +48,8 @@ hipError_t launch_quantize(hipStream_t s, const uint16_t* x, int64_t rows_in, in
                            const int32_t* dst_rows, int32_t fanout, uint8_t* q, float* scales);
 hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, bool gathered, const int32_t* offsets,
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2,
-                             const float* s1, const float* s3, const float* s2, float* y_perm);
+                             const float* s1, const float* s3, const float* s2, float* y_perm, int16_t* yq,
+                             float* ys);
 hipError_t launch_linear(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t rows, int32_t K,
                          const uint8_t* Wq, const float* ws, int32_t NOUT, float* y);
 hipError_t launch_quantize_weights(hipStream_t s, const uint16_t* w, int64_t rows, int32_t cols, uint8_t* q,
@@ -57,5 +58,7 @@ size_t ffn_work_bytes(int max_tiles, int F, int d);
 size_t route_workspace_bytes(int E, int d);
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm,
                           const float* topk_w, uint16_t* y);
+hipError_t launch_combine_i16(moe_ctx* c, const int16_t* yq, const float* ys, const int32_t* inv_perm,
+                              const float* topk_w, uint16_t* y);
 
 }  // namespace moe355

@@ -35,6 +35,8 @@ class MoELayer:
         self.xs_tok = torch.empty((d // 128, max(T, 1)), dtype=torch.float32, device=dev)
         self.y_perm = torch.empty((N, d), dtype=torch.float32, device=dev)
         self.y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
+        self.yq = None          # 16-bit expert outputs [N,d] and their scales [N,d/128], allocated on first use
+        self.ys = None
 
     def close(self):
         if getattr(self, "ctx", None):
@@ -77,10 +79,27 @@ class MoELayer:
     def combine(self):
         B.moe_combine(self.ctx, self.y_perm, self.inv_perm, self.topk_w, self.y)
 
+    def expert_ffn_gather_i16(self, w: Dict[str, torch.Tensor]):
+        if self.yq is None:
+            N = max(self.N, 1)
+            self.yq = torch.empty((N, self.d), dtype=torch.int16, device=self.device)
+            self.ys = torch.empty((N, self.d // 128), dtype=torch.float32, device=self.device)
+        B.moe_expert_ffn_fp8_gather_i16(self.ctx, self.xq_tok, self.xs_tok, self.offsets, w["W1q"], w["W3q"],
+                                        w["W2q"], w["s1"], w["s3"], w["s2"], self.yq, self.ys)
+
+    def combine_i16(self):
+        B.moe_combine_i16(self.ctx, self.yq, self.ys, self.inv_perm, self.topk_w, self.y)
+
     # ---- whole layer ----------------------------------------------------------------
     # `fused` = True: activations quantised once per token, gathered inside the gate/up GEMM;
-    # False: the expert-ordered copy xq/xs is materialised first (same results bit for bit)
+    # False: the expert-ordered copy xq/xs is materialised first (same results bit for bit);
+    # "i16": as True, with the expert outputs stored as 16-bit block-scaled rows between the down GEMM and the combine
     def _ffn(self, x, w, fused):
+        if fused == "i16":
+            self.quantize_tokens(x)
+            self.expert_ffn_gather_i16(w)
+            self.combine_i16()
+            return self.y
         if fused:
             self.quantize_tokens(x)
             self.expert_ffn_gather(w)

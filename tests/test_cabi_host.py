@@ -64,6 +64,8 @@ def test_null_arguments_are_rejected(lib):
     assert lib.moe_expert_ffn_fp8_gather(None, None, None, None, None, None, None, None, None, None, None) == -1
     assert lib.moe_expert_ffn_fp8(*([None] * 11)) == -1
     assert lib.moe_combine(*([None] * 5)) == -1
+    assert lib.moe_combine_i16(*([None] * 6)) == -1
+    assert lib.moe_expert_ffn_fp8_gather_i16(*([None] * 12)) == -1
     assert lib.moe_check_ids(None) == -1
 
 

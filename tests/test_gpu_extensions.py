@@ -198,3 +198,49 @@ def test_gather_fused_ffn_is_bit_identical_to_the_materialised_path(gpu_lib, cfg
         assert rel <= 2e-3
     finally:
         layer.close()
+
+
+# --------------------------------------------------------------------------- 16-bit expert outputs
+@pytest.mark.parametrize("cfg", [CONFIGS[0], CONFIGS[1],
+                                 MoEConfig("q_ragged", T=333, d=384, E=40, k=5, F=384, modes=("routed",), seed=43),
+                                 MoEConfig("q_skew", T=900, d=128, E=6, k=2, F=256, modes=("routed",), seed=44),
+                                 MoEConfig("q_k3", T=257, d=640, E=9, k=3, F=128, modes=("routed",), seed=45)],
+                         ids=lambda c: c.name)
+def test_i16_expert_outputs(gpu_lib, cfg):
+    """Down projection with 16-bit block-scaled output + its combine.  Codes and scales must be exactly the oracle's
+    row quantisation of the fp32 rows the plain path writes (same accumulators); the combine over them must match
+    the oracle's combine of the dequantised rows; the layer output keeps the 2e-3 bar against the oracle."""
+    inp = make_inputs(cfg)
+    dv = {k: (v.cuda() if isinstance(v, torch.Tensor) else v) for k, v in inp.items()}
+    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+    try:
+        layer.forward_routed(dv["x"], dv["W_r"], None, dv, fused=True)
+        torch.cuda.synchronize()
+        y_fp32_path = layer.y.float().cpu().numpy()
+        y_perm = layer.y_perm.cpu().numpy()[:cfg.N].astype(np.float64)
+        layer.y.zero_()
+        layer.forward_routed(dv["x"], dv["W_r"], None, dv, fused="i16")
+        torch.cuda.synchronize()
+        yq_g = layer.yq.cpu().numpy()[:cfg.N]
+        ys_g = layer.ys.cpu().numpy()[:cfg.N]
+        yq_o, ys_o = om.quantize_rows_i16(y_perm)
+        assert np.array_equal(ys_g, ys_o)
+        assert np.array_equal(yq_g, yq_o)
+        # combine alone: the oracle's combine on the dequantised rows (fp32 vs fp64 sums may flip a bf16 rounding)
+        idx, w = layer.topk_idx.cpu().numpy(), layer.topk_w.cpu().numpy()
+        inv_perm = layer.inv_perm.cpu().numpy()
+        _, bits_iso = om.combine(om.dequantize_rows_i16(yq_g, ys_g), inv_perm, w)
+        iso = ff.bf16_bits_to_f64(bits_iso)
+        y_g = layer.y.float().cpu().numpy()
+        flips = float((y_g != iso).mean())
+        assert flips < 2e-3 and _rel_l2(y_g, iso) <= 1e-6 + 0.01 * np.sqrt(flips)
+        # against the fp32-row path and against the oracle's layer
+        drift = _rel_l2(y_g, y_fp32_path)
+        ref = om.moe_layer(_bits(inp["x"]), cfg.E, idx, w,
+                           *[inp[n].numpy() for n in ("W1q", "W3q", "W2q", "s1", "s3", "s2")])
+        rel = _rel_l2(y_g, ff.bf16_bits_to_f64(ref["y_bits"]))
+        print(f"[{cfg.name}] i16 path: vs fp32-row path {drift:.3e}, layer rel-L2 vs oracle {rel:.3e}")
+        assert drift <= 2.5e-3          # both are bf16-rounded: differences are single bf16 flips
+        assert rel <= 2e-3
+    finally:
+        layer.close()

@@ -161,7 +161,29 @@ def _fullsize(gpu_lib, cfg, mode, n_tokens_e2e):
         hq_f, hs_f = layer.hidden()
         assert torch.equal(hq_mat, hq_f) and torch.equal(hs_mat.view(torch.int32), hs_f.view(torch.int32))
         assert torch.equal(y_mat.view(torch.int16), layer.y.view(torch.int16))
-        return layer.y.clone()
+
+        # the 16-bit expert-output path at full size: sampled rows of codes and scales are exactly the oracle's
+        # row quantisation of the fp32 rows above, and the same end-to-end tokens keep the bar
+        rows_s = np.unique(rng.integers(0, cfg.N, size=512))
+        yp_rows = layer.y_perm[torch.from_numpy(rows_s).to(dev)].cpu().numpy().astype(np.float64)
+        layer.y.zero_()
+        layer._ffn(inp["x"], inp, fused="i16")
+        torch.cuda.synchronize()
+        yq_o, ys_o = om.quantize_rows_i16(yp_rows)
+        sel = torch.from_numpy(rows_s).to(dev)
+        assert np.array_equal(layer.yq[sel].cpu().numpy(), yq_o)
+        assert np.array_equal(layer.ys[sel].cpu().numpy(), ys_o)
+        got16 = layer.y[torch.from_numpy(e2e).to(dev)].float().cpu().numpy()
+        num16 = np.sum((got16 - ref) ** 2, axis=1)
+        est16 = float(np.sqrt(num16.sum() / den))
+        se16 = float(0.5 * np.sqrt(e2e.size * np.var(num16)) / den / max(est16, 1e-30))
+        drift = _rel_l2(layer.y.float().cpu().numpy(), y_mat.float().cpu().numpy())
+        print(f"[{cfg.name}/{mode}] 16-bit expert outputs: layer rel-L2 {est16:.3e} +- {se16:.1e}; whole tensor vs the "
+              f"fp32-row path {drift:.3e}")
+        assert est16 - 2.0 * se16 <= REL_L2_BAR
+        assert drift <= 1e-3
+        layer.yq = layer.ys = None
+        return y_mat
     finally:
         layer.close()
 
