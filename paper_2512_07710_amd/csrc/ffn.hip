@@ -25,7 +25,9 @@
 //
 // GEMM1: staged rows of wave wf are [64 gate rows | 64 up rows] of the same features;
 //        epilogue h = silu(g)*u, re-quantised to e4m3 with one scale per (row, 128 features).
-// GEMM2: staged rows are 256 consecutive output features; epilogue fp32 store.
+// GEMM2: staged rows are 256 consecutive output features; epilogue: fp32 rows (or 16-bit codes with one
+//        scale per row and 128 features), turned through LDS so that every row is stored in contiguous
+//        256-byte pieces.
 #include "moe_internal.hpp"
 
 namespace moe355 {
