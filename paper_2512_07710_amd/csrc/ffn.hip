@@ -133,15 +133,6 @@ __device__ inline v8i lds_operand(const uint8_t* row, uint32_t o0, uint32_t o1) 
     return r;
 }
 
-__device__ inline float clamp448(float v) { return fminf(fmaxf(v, -448.f), 448.f); }
-
-__device__ inline uint32_t pack4_e4m3(float a, float b, float c, float d) {
-    int p = 0;
-    p = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(a), clamp448(b), p, false);
-    p = __builtin_amdgcn_cvt_pk_fp8_f32(clamp448(c), clamp448(d), p, true);
-    return (uint32_t)p;
-}
-
 // ------------------------------------------------------------------ GEMM kernel
 // GATED = true : Wa = W1, Wb = W3 [E, NOUT, K]; feature tile = 128 features (gate + up rows)
 // GATED = false: Wa = W2 [E, NOUT, K]; feature tile = 256 output features
@@ -482,15 +473,27 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                 const int p = wk.row0 + trow;
                 const float am = fmaxf(amax[ts], s_amax[(wf ^ 1) * X_ROWS + trow]);
                 const float sc = (am == 0.f) ? 1.0f : am / 448.0f;
+                // h / sc, correctly rounded, for 32 values per token: a reciprocal refined once, then the
+                // quotient estimate corrected by its exact remainder (three instructions instead of a full
+                // division each; equal to the division wherever sc is far from the ends of the fp32 range,
+                // and the plain division elsewhere).  |h / sc| <= 448 up to one rounding, so no clamp.
+                float inv = __builtin_amdgcn_rcpf(sc);
+                inv = fmaf(fmaf(-sc, inv, 1.0f), inv, inv);
+                const bool mid_range = sc > 1e-30f && sc < 1e30f;
+                auto quot = [&](float hv) {
+                    const float q0 = hv * inv;
+                    return mid_range ? fmaf(fmaf(-q0, sc, hv), inv, q0) : hv / sc;
+                };
                 if (p < row_end) {
                     uint8_t* dst = hq + (size_t)p * NOUT + f0 + wf * 64 + half * 4;
 #pragma unroll
                     for (int s = 0; s < 2; ++s)
 #pragma unroll
                         for (int r4 = 0; r4 < 4; ++r4) {
-                            const uint32_t code = pack4_e4m3(h[ts][s][r4 * 4] / sc, h[ts][s][r4 * 4 + 1] / sc,
-                                                             h[ts][s][r4 * 4 + 2] / sc, h[ts][s][r4 * 4 + 3] / sc);
-                            *reinterpret_cast<uint32_t*>(dst + s * 32 + r4 * 8) = code;
+                            int code = 0;
+                            code = __builtin_amdgcn_cvt_pk_fp8_f32(quot(h[ts][s][r4 * 4]), quot(h[ts][s][r4 * 4 + 1]), code, false);
+                            code = __builtin_amdgcn_cvt_pk_fp8_f32(quot(h[ts][s][r4 * 4 + 2]), quot(h[ts][s][r4 * 4 + 3]), code, true);
+                            *reinterpret_cast<uint32_t*>(dst + s * 32 + r4 * 8) = (uint32_t)code;
                         }
                     if (half == 0 && wf == 0) hs[(size_t)wk.ft * n_rows + p] = sc;
                 }
