@@ -68,6 +68,40 @@ __global__ __launch_bounds__(256) void split_router_weights(const float* __restr
     }
 }
 
+// s_waitcnt vmcnt(n): the immediate has to be a literal in the asm text, so one case per value; n is known
+// after unrolling and the switch folds away.  Values above the largest case wait for everything.
+__device__ inline void wait_vm(int n) {
+    switch (n) {
+        case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(1)" ::: "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(2)" ::: "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(3)" ::: "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(4)" ::: "memory"); break;
+        case 5: asm volatile("s_waitcnt vmcnt(5)" ::: "memory"); break;
+        case 6: asm volatile("s_waitcnt vmcnt(6)" ::: "memory"); break;
+        case 7: asm volatile("s_waitcnt vmcnt(7)" ::: "memory"); break;
+        case 8: asm volatile("s_waitcnt vmcnt(8)" ::: "memory"); break;
+        case 9: asm volatile("s_waitcnt vmcnt(9)" ::: "memory"); break;
+        case 10: asm volatile("s_waitcnt vmcnt(10)" ::: "memory"); break;
+        case 11: asm volatile("s_waitcnt vmcnt(11)" ::: "memory"); break;
+        case 12: asm volatile("s_waitcnt vmcnt(12)" ::: "memory"); break;
+        case 13: asm volatile("s_waitcnt vmcnt(13)" ::: "memory"); break;
+        case 14: asm volatile("s_waitcnt vmcnt(14)" ::: "memory"); break;
+        case 15: asm volatile("s_waitcnt vmcnt(15)" ::: "memory"); break;
+        case 16: asm volatile("s_waitcnt vmcnt(16)" ::: "memory"); break;
+        case 17: asm volatile("s_waitcnt vmcnt(17)" ::: "memory"); break;
+        case 18: asm volatile("s_waitcnt vmcnt(18)" ::: "memory"); break;
+        case 19: asm volatile("s_waitcnt vmcnt(19)" ::: "memory"); break;
+        case 20: asm volatile("s_waitcnt vmcnt(20)" ::: "memory"); break;
+        case 21: asm volatile("s_waitcnt vmcnt(21)" ::: "memory"); break;
+        case 22: asm volatile("s_waitcnt vmcnt(22)" ::: "memory"); break;
+        case 23: asm volatile("s_waitcnt vmcnt(23)" ::: "memory"); break;
+        case 24: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
+    }
+}
+#define WAIT_VM(N) wait_vm(N)
+
 // NS: 32-expert sub-tiles per wave (E_pad = 128*NS).  TS: 32-token sub-tiles per block (32*TS tokens):
 // four for large batches, one when the batch would otherwise fill only a fraction of the compute units.
 // IDS = false: top-k selection.  IDS = true (ids-only Router Replay): the k expert ids of every token are
@@ -163,19 +197,14 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
             // complete in issue order, so "at most as many outstanding as were issued since" means they
             // have arrived.  (Written out by hand: the steady-state loop gets no automatic wait for
             // values loaded in an earlier iteration and consumed by asm.)
-            // Three groups of 3*NS loads have been issued since, except in the last chunk, whose step ks
-            // is followed by 3 - ks groups only.
-            if (kc + 1 < nchunks || ks == 0) {
-                if (NS == 2) asm volatile("s_waitcnt vmcnt(18)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(9)" ::: "memory");
-            } else if (ks == 1) {
-                if (NS == 2) asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-            } else if (ks == 2) {
-                if (NS == 2) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-                else asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+            // Issued since: the weight groups of the next three steps (3*NS loads each; in the last chunk step
+            // ks is followed by 3 - ks groups only) and, for steps 0..2 of a chunk, the TS copies of the next
+            // chunk that went out at this chunk's top: those may all stay in flight.
+            if (kc + 1 < nchunks) {
+                if (ks < 3) WAIT_VM(3 * 3 * NS + TS);
+                else WAIT_VM(3 * 3 * NS);
             } else {
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                WAIT_VM((3 - ks) * 3 * NS);
             }
 #pragma unroll
             for (int s = 0; s < NS; ++s)
@@ -276,25 +305,28 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     }
     __syncthreads();
 
-    // ---- merge the four waves' candidates, softmax, store: one thread per token
+    // ---- merge the four waves' candidates, softmax, store: one thread per token.  Every wave's list is already in
+    //      selection order (descending score, lower index first), so the merge only compares the four list heads.
     if (tid < RT && t0 + tid < T) {
         const float2* mine = cand + (size_t)tid * 4 * MAX_K;
-        uint64_t used = 0ull;
+        int head0 = 0, head1 = 0, head2 = 0, head3 = 0;
         float sel_logit[MAX_K];
         int sel_idx[MAX_K];
         float m = -INFINITY;
         for (int j = 0; j < k; ++j) {
             float bs = 0.f, bl = 0.f;
-            int bi = NO_CAND, bq = 0;
-            for (int q = 0; q < 4 * MAX_K; ++q) {
-                if ((q & (MAX_K - 1)) >= k || ((used >> q) & 1ull)) continue;
-                const float2 c = mine[q];
+            int bi = NO_CAND, bw = 0;
+#pragma unroll
+            for (int w = 0; w < 4; ++w) {
+                const int h = w == 0 ? head0 : w == 1 ? head1 : w == 2 ? head2 : head3;
+                if (h >= k) continue;
+                const float2 c = mine[w * MAX_K + h];
                 const int e = __float_as_int(c.y);
-                if (e == NO_CAND) continue;
+                if (e == NO_CAND) continue;                    // this wave's experts are used up
                 const float sc = c.x + (bias ? bias[e] : 0.f);
-                if (bi == NO_CAND || sc > bs || (sc == bs && e < bi)) { bs = sc; bl = c.x; bi = e; bq = q; }
+                if (bi == NO_CAND || sc > bs || (sc == bs && e < bi)) { bs = sc; bl = c.x; bi = e; bw = w; }
             }
-            used |= 1ull << bq;
+            head0 += bw == 0; head1 += bw == 1; head2 += bw == 2; head3 += bw == 3;
             sel_logit[j] = bl;
             sel_idx[j] = bi;
             m = fmaxf(m, bl);
