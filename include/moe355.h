@@ -7,7 +7,7 @@
  *     rollout time are recorded and reused verbatim when the layer is evaluated
  *     again, instead of being recomputed.
  *   - FP8 rollout (section 3.1.2): weights arrive block-wise quantised to FP8
- *     and activations are quantised to FP8 on the fly, for Linear and MoE layers.
+ *     and activations are quantised to FP8 on the fly, in the dense linear layers as well as the MoE layers.
  * The paper gives no formulas for the layer; each entry point below states the
  * definition it implements.
  *
@@ -127,7 +127,7 @@ int moe_quantize_fp8(moe_ctx* ctx, const uint16_t* x_bf16, int64_t rows_in, int3
 int moe_quantize_weights_fp8(moe_ctx* ctx, const uint16_t* w_bf16, int64_t rows, int32_t cols,
                              uint8_t* q, float* scales);
 
-/* Dense block-scaled FP8 linear layer (section 3.1.2 applies FP8 to "Linear and MoE layers"):
+/* Dense block-scaled FP8 linear layer (section 3.1.2 applies FP8 to the dense linear layers as well as to the MoE layers):
  *   y[p,n] = sum_kb xs[kb,p]*ws[n/128,kb] * sum_{c in block kb} xq[p,c]*Wq[n,c],  fp32 out.
  * The grouped down-projection kernel with one group that owns every row.
  *   xq [rows,K] u8 and xs [K/128][rows] f32 as written by moe_quantize_fp8 (dst_rows = NULL);
