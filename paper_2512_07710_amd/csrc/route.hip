@@ -22,7 +22,6 @@ typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
-constexpr int RKC = 64;          // hidden columns per staged activation chunk (128 bytes per row)
 constexpr int NO_CAND = 0x7FFFFFFF;
 
 __device__ inline uint32_t f32_to_bf16_rne_bits(float v) {
@@ -69,7 +68,7 @@ __global__ __launch_bounds__(256) void split_router_weights(const float* __restr
 }
 
 // s_waitcnt vmcnt(n): the immediate has to be a literal in the asm text, so one case per value; n is known
-// after unrolling and the switch folds away.  Values above the largest case wait for everything.
+// after unrolling and the switch folds away.  Values beyond the 6-bit field wait for everything.
 __device__ inline void wait_vm(int n) {
     switch (n) {
         case 0: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
@@ -97,6 +96,45 @@ __device__ inline void wait_vm(int n) {
         case 22: asm volatile("s_waitcnt vmcnt(22)" ::: "memory"); break;
         case 23: asm volatile("s_waitcnt vmcnt(23)" ::: "memory"); break;
         case 24: asm volatile("s_waitcnt vmcnt(24)" ::: "memory"); break;
+        case 25: asm volatile("s_waitcnt vmcnt(25)" ::: "memory"); break;
+        case 26: asm volatile("s_waitcnt vmcnt(26)" ::: "memory"); break;
+        case 27: asm volatile("s_waitcnt vmcnt(27)" ::: "memory"); break;
+        case 28: asm volatile("s_waitcnt vmcnt(28)" ::: "memory"); break;
+        case 29: asm volatile("s_waitcnt vmcnt(29)" ::: "memory"); break;
+        case 30: asm volatile("s_waitcnt vmcnt(30)" ::: "memory"); break;
+        case 31: asm volatile("s_waitcnt vmcnt(31)" ::: "memory"); break;
+        case 32: asm volatile("s_waitcnt vmcnt(32)" ::: "memory"); break;
+        case 33: asm volatile("s_waitcnt vmcnt(33)" ::: "memory"); break;
+        case 34: asm volatile("s_waitcnt vmcnt(34)" ::: "memory"); break;
+        case 35: asm volatile("s_waitcnt vmcnt(35)" ::: "memory"); break;
+        case 36: asm volatile("s_waitcnt vmcnt(36)" ::: "memory"); break;
+        case 37: asm volatile("s_waitcnt vmcnt(37)" ::: "memory"); break;
+        case 38: asm volatile("s_waitcnt vmcnt(38)" ::: "memory"); break;
+        case 39: asm volatile("s_waitcnt vmcnt(39)" ::: "memory"); break;
+        case 40: asm volatile("s_waitcnt vmcnt(40)" ::: "memory"); break;
+        case 41: asm volatile("s_waitcnt vmcnt(41)" ::: "memory"); break;
+        case 42: asm volatile("s_waitcnt vmcnt(42)" ::: "memory"); break;
+        case 43: asm volatile("s_waitcnt vmcnt(43)" ::: "memory"); break;
+        case 44: asm volatile("s_waitcnt vmcnt(44)" ::: "memory"); break;
+        case 45: asm volatile("s_waitcnt vmcnt(45)" ::: "memory"); break;
+        case 46: asm volatile("s_waitcnt vmcnt(46)" ::: "memory"); break;
+        case 47: asm volatile("s_waitcnt vmcnt(47)" ::: "memory"); break;
+        case 48: asm volatile("s_waitcnt vmcnt(48)" ::: "memory"); break;
+        case 49: asm volatile("s_waitcnt vmcnt(49)" ::: "memory"); break;
+        case 50: asm volatile("s_waitcnt vmcnt(50)" ::: "memory"); break;
+        case 51: asm volatile("s_waitcnt vmcnt(51)" ::: "memory"); break;
+        case 52: asm volatile("s_waitcnt vmcnt(52)" ::: "memory"); break;
+        case 53: asm volatile("s_waitcnt vmcnt(53)" ::: "memory"); break;
+        case 54: asm volatile("s_waitcnt vmcnt(54)" ::: "memory"); break;
+        case 55: asm volatile("s_waitcnt vmcnt(55)" ::: "memory"); break;
+        case 56: asm volatile("s_waitcnt vmcnt(56)" ::: "memory"); break;
+        case 57: asm volatile("s_waitcnt vmcnt(57)" ::: "memory"); break;
+        case 58: asm volatile("s_waitcnt vmcnt(58)" ::: "memory"); break;
+        case 59: asm volatile("s_waitcnt vmcnt(59)" ::: "memory"); break;
+        case 60: asm volatile("s_waitcnt vmcnt(60)" ::: "memory"); break;
+        case 61: asm volatile("s_waitcnt vmcnt(61)" ::: "memory"); break;
+        case 62: asm volatile("s_waitcnt vmcnt(62)" ::: "memory"); break;
+        case 63: asm volatile("s_waitcnt vmcnt(63)" ::: "memory"); break;
         default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;
     }
 }
@@ -104,9 +142,11 @@ __device__ inline void wait_vm(int n) {
 
 // NS: 32-expert sub-tiles per wave (E_pad = 128*NS).  TS: 32-token sub-tiles per block (32*TS tokens):
 // four for large batches, one when the batch would otherwise fill only a fraction of the compute units.
+// KS: K steps (of 16 columns) per staged activation chunk = depth of the weight-operand ring: 4 for the large
+// token tile (registers), 8 for the small ones, whose K loop is a chain of L2 round trips otherwise.
 // IDS = false: top-k selection.  IDS = true (ids-only Router Replay): the k expert ids of every token are
 // given in logged_idx; their logits are picked out of the same accumulators and only the softmax is new.
-template <int NS, int TS, bool IDS>
+template <int NS, int TS, int KS, bool IDS>
 __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __restrict__ x,
                                                             const uint16_t* __restrict__ planes,
                                                             const float* __restrict__ bias,
@@ -114,15 +154,22 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
                                                             int E, int k, int32_t* __restrict__ topk_idx,
                                                             float* __restrict__ topk_w) {
     constexpr int RT = 32 * TS;                                // tokens per block
-    // two activation stages of RT rows x 128 bytes; the candidate lists [token][wave][MAX_K]
-    // of {logit, expert id} reuse the storage afterwards
+    constexpr int PANELS = KS / 4;                             // a chunk is staged as panels of RT rows x 128 bytes (64 columns)
+    constexpr int STAGE = PANELS * RT * 128;                   // bytes of one staged chunk
+    constexpr int AH = KS - 1;                                 // K steps the weight loads run ahead
+    constexpr int L = 3 * NS;                                  // weight loads per K step and wave
+    constexpr int C = PANELS * TS;                             // activation copies per chunk and wave
+    static_assert(KS == 4 || KS == 8, "a ring slot is a step's position inside its chunk");
+    // two activation stages; the candidate lists [token][wave][MAX_K] of {logit, expert id} reuse the
+    // storage afterwards
     __shared__ __attribute__((aligned(16))) uint8_t smem[RT * 4 * MAX_K * 8];
-    static_assert(RT * 4 * MAX_K * 8 >= 2 * RT * 128, "stages fit");
+    static_assert(RT * 4 * MAX_K * 8 >= 2 * STAGE, "stages fit");
+    static_assert(AH * L + C <= 63 && KS * L <= 63, "wait counts fit the 6-bit field");
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int t0 = blockIdx.x * RT;
-    const int nk = d / 16, nchunks = d / RKC;
+    const int nk = d / 16, nchunks = nk / KS;
 
     // activation staging by direct-to-LDS copies: wave w, copy j < TS brings rows (TS*w+j)*8 .. +7 of the chunk;
     // lane i -> row i/8, LDS chunk slot i%8, which receives global 16-byte chunk
@@ -136,12 +183,14 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) uint8_t*)smem;
     auto issue_x = [&](int kc) {
-        const uint8_t* src = reinterpret_cast<const uint8_t*>(x) + (size_t)kc * (RKC * 2);
-        const uint32_t dst = lds0 + (kc & 1) * RT * 128 + wave * TS * 1024;
+        const uint8_t* src = reinterpret_cast<const uint8_t*>(x) + (size_t)kc * (KS * 32);
+        const uint32_t dst = lds0 + (kc & 1) * STAGE + wave * TS * 1024;
 #pragma unroll
-        for (int j = 0; j < TS; ++j)
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :: "s"(dst + j * 1024), "v"(xoff[j]), "s"(src) : "memory");
+        for (int pn = 0; pn < PANELS; ++pn)
+#pragma unroll
+            for (int j = 0; j < TS; ++j)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                             :: "s"(dst + pn * RT * 128 + j * 1024), "v"(xoff[j]), "s"(src + pn * 128) : "memory");
     };
     const v4i* wsrc[NS];
 #pragma unroll
@@ -158,10 +207,10 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[s][ts][r] = 0.f;
 
-    // Weight operands run three K steps ahead of the matrix cores in a ring of four register sets
-    // (a K step is 16 columns; a staged activation chunk holds four of them, so the ring slot of a
-    // step is its position inside the chunk): an L2 round trip is hidden behind ~70 MFMAs.
-    v4i a[4][NS][3];
+    // Weight operands run KS - 1 K steps ahead of the matrix cores in a ring of KS register sets
+    // (a K step is 16 columns; a staged activation chunk holds KS of them, so the ring slot of a
+    // step is its position inside the chunk).
+    v4i a[KS][NS][3];
     auto load_a = [&](int slot, int kk) {
 #pragma unroll
         for (int s = 0; s < NS; ++s)
@@ -169,42 +218,40 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
             for (int p = 0; p < 3; ++p) a[slot][s][p] = wsrc[s][((size_t)kk * 3 + p) * 64];
     };
     issue_x(0);
-    load_a(0, 0);
-    load_a(1, 1);
-    load_a(2, 2);
+#pragma unroll
+    for (int i = 0; i < AH; ++i) load_a(i, i);                 // nk >= 8 >= AH: d is a multiple of 128
 
     for (int kc = 0; kc < nchunks; ++kc) {
         // chunk kc must have landed.  Vector-memory operations complete in issue order: after the copies
-        // of chunk kc this wave has issued exactly four K steps of weight loads (3*NS each), except
+        // of chunk kc this wave has issued exactly KS K steps of weight loads (L each), except
         // before the first chunk.
-        if (kc == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        else if (NS == 2) asm volatile("s_waitcnt vmcnt(24)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(12)" ::: "memory");
+        if (kc == 0) WAIT_VM(0); else WAIT_VM(KS * L);
         __syncthreads();                                       // landed for everybody; chunk kc-1 fully consumed
         if (kc + 1 < nchunks) issue_x(kc + 1);
-        const uint8_t* stage = smem + (kc & 1) * RT * 128;
+        const uint8_t* stage = smem + (kc & 1) * STAGE;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const int kk = kc * 4 + ks;
-            if (kk + 3 < nk) load_a((ks + 3) & 3, kk + 3);
+        for (int ks = 0; ks < KS; ++ks) {
+            const int kk = kc * KS + ks;
+            if (kk + AH < nk) load_a((ks + AH) % KS, kk + AH);
             v4i b[TS];
 #pragma unroll
             for (int ts = 0; ts < TS; ++ts) {
                 const int row = ts * 32 + l32;
-                b[ts] = *reinterpret_cast<const v4i*>(stage + row * 128 + (((ks * 2 + half) ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
+                b[ts] = *reinterpret_cast<const v4i*>(stage + (ks >> 2) * RT * 128 + row * 128 +
+                                                      ((((ks & 3) * 2 + half) ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
             }
-            // The weight operands of this K step were requested three steps ago; vector-memory operations
+            // The weight operands of this K step were requested AH steps ago; vector-memory operations
             // complete in issue order, so "at most as many outstanding as were issued since" means they
             // have arrived.  (Written out by hand: the steady-state loop gets no automatic wait for
             // values loaded in an earlier iteration and consumed by asm.)
-            // Issued since: the weight groups of the next three steps (3*NS loads each; in the last chunk step
-            // ks is followed by 3 - ks groups only) and, for steps 0..2 of a chunk, the TS copies of the next
-            // chunk that went out at this chunk's top: those may all stay in flight.
+            // Issued since: the weight groups of the next AH steps (in the last chunk step ks is followed
+            // by KS - 1 - ks groups only) and, for every step of a chunk but the last, the C copies of the
+            // next chunk that went out at this chunk's top: those may all stay in flight.
             if (kc + 1 < nchunks) {
-                if (ks < 3) WAIT_VM(3 * 3 * NS + TS);
-                else WAIT_VM(3 * 3 * NS);
+                if (ks < KS - 1) WAIT_VM(AH * L + C);
+                else WAIT_VM(AH * L);
             } else {
-                WAIT_VM((3 - ks) * 3 * NS);
+                WAIT_VM((KS - 1 - ks) * L);
             }
 #pragma unroll
             for (int s = 0; s < NS; ++s)
@@ -359,7 +406,7 @@ hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const f
     const int TS = D.T >= 256 * 128 ? 4 : D.T >= 256 * 64 ? 2 : 1;
     const int grid = (D.T + 32 * TS - 1) / (32 * TS);
 #define MOE_ROUTE_LAUNCH(NS_, TS_, IDS_)                                                                    \
-    hipLaunchKernelGGL((route_mfma_kernel<NS_, TS_, IDS_>), dim3(grid), dim3(256), 0, c->stream, x,         \
+    hipLaunchKernelGGL((route_mfma_kernel<NS_, TS_, (TS_ == 4 ? 4 : 8), IDS_>), dim3(grid), dim3(256), 0, c->stream, x,         \
                        c->router_planes, bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w)
 #define MOE_ROUTE_TS(NS_, IDS_)                                                                             \
     do {                                                                                                    \

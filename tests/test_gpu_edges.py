@@ -81,3 +81,27 @@ def test_empty_batch(gpu_lib):
         torch.cuda.synchronize()
     finally:
         gpu_lib.moe_destroy(ctx)
+
+
+@pytest.mark.parametrize("T,d,E,k", [(16500, 256, 16, 2), (20000, 128, 200, 4), (33000, 128, 40, 3)])
+def test_route_token_tile_variants(gpu_lib, T, d, E, k):
+    """Routing only, at batch sizes that select the 64-token tile (16384 <= T < 32768) and the 128-token tile with a
+    ragged last block; ids, weights and the permutation against the oracle."""
+    from workloads import make_inputs
+    from test_gpu_parity import _compare_routing, _check_permutation, _host
+    cfg = MoEConfig("tiles", T=T, d=d, E=E, k=k, F=128, modes=("routed",), seed=T % 97)
+    inp = make_inputs(cfg, with_experts=False)
+    h = _host(inp)
+    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+    try:
+        layer.route(inp["x"].cuda(), inp["W_r"].cuda(), None)
+        torch.cuda.synchronize()
+        _compare_routing(h, layer, None)
+        _check_permutation(layer.topk_idx.cpu().numpy(), cfg.E, layer)
+        # ids-only replay of the router's own ids reproduces its weights bit for bit
+        idx, w = layer.topk_idx.clone(), layer.topk_w.clone()
+        layer.route_replay_ids(inp["x"].cuda(), inp["W_r"].cuda(), idx)
+        torch.cuda.synchronize()
+        assert torch.equal(layer.topk_idx, idx) and torch.equal(layer.topk_w.view(torch.int32), w.view(torch.int32))
+    finally:
+        layer.close()
