@@ -142,8 +142,8 @@ __device__ inline void wait_vm(int n) {
 
 // NS: 32-expert sub-tiles per wave (E_pad = 128*NS).  TS: 32-token sub-tiles per block (32*TS tokens):
 // four for large batches, one when the batch would otherwise fill only a fraction of the compute units.
-// KS: K steps (of 16 columns) per staged activation chunk = depth of the weight-operand ring: 4 for the large
-// token tile (registers), 8 for the small ones, whose K loop is a chain of L2 round trips otherwise.
+// KS: K steps (of 16 columns) per staged activation chunk = depth of the weight-operand ring (8 in every launch:
+// with 4 the K loop of the small token tiles is a chain of L2 round trips).
 // IDS = false: top-k selection.  IDS = true (ids-only Router Replay): the k expert ids of every token are
 // given in logged_idx; their logits are picked out of the same accumulators and only the softmax is new.
 template <int NS, int TS, int KS, bool IDS>
@@ -406,7 +406,7 @@ hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const f
     const int TS = D.T >= 256 * 128 ? 4 : D.T >= 256 * 64 ? 2 : 1;
     const int grid = (D.T + 32 * TS - 1) / (32 * TS);
 #define MOE_ROUTE_LAUNCH(NS_, TS_, IDS_)                                                                    \
-    hipLaunchKernelGGL((route_mfma_kernel<NS_, TS_, (TS_ == 4 ? 4 : 8), IDS_>), dim3(grid), dim3(256), 0, c->stream, x,         \
+    hipLaunchKernelGGL((route_mfma_kernel<NS_, TS_, 8, IDS_>), dim3(grid), dim3(256), 0, c->stream, x,         \
                        c->router_planes, bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w)
 #define MOE_ROUTE_TS(NS_, IDS_)                                                                             \
     do {                                                                                                    \
