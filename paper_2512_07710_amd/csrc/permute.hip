@@ -7,7 +7,8 @@
 //   2. scan_chunks: one block turns the per-chunk histograms into exclusive prefix
 //      sums over chunks (per expert) and the expert totals into offsets[0..E].
 //   3. scatter: position = offsets[e] + prefix[chunk][e] + rank; writes perm/inv_perm.
-// The result is unique (stable), so it can be compared bit for bit.
+// The result is unique (stable), so it can be compared bit for bit.  Batches of at most PERM_CHUNK
+// assignments take one fused launch instead (permute_one_chunk).
 #include "moe_internal.hpp"
 
 namespace moe355 {
@@ -132,6 +133,84 @@ __global__ __launch_bounds__(256) void scatter(const int32_t* __restrict__ ids, 
     row_token[pos] = i / k;                             // read by the gathering gate/up GEMM
 }
 
+// N <= PERM_CHUNK: the three steps in one block and one launch (decode-sized batches, where the launches
+// themselves are most of the time).  Same ranking as chunk_hist_rank, then the scan over experts and the
+// scatter from registers.
+__global__ __launch_bounds__(256) void permute_one_chunk(const int32_t* __restrict__ ids, int N, int E,
+                                                         int32_t* __restrict__ ids_copy,
+                                                         const float* __restrict__ w_in, float* __restrict__ w_copy,
+                                                         int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
+                                                         int32_t* __restrict__ inv_perm,
+                                                         int32_t* __restrict__ row_token, int k,
+                                                         int32_t* __restrict__ flags) {
+    constexpr int PER_WAVE = PERM_CHUNK / 4;
+    __shared__ int32_t s_cnt[4][MAX_E];
+    __shared__ int32_t s_off[MAX_E];                  // inclusive scan of the expert totals
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    for (int i = tid; i < 4 * MAX_E; i += 256) (&s_cnt[0][0])[i] = 0;
+    __syncthreads();
+    int32_t my_id[PER_WAVE / 64], my_rank[PER_WAVE / 64];
+    const uint64_t lower = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int st = 0; st < PER_WAVE / 64; ++st) {
+        const int i = wave * PER_WAVE + st * 64 + lane;
+        int32_t v = -1;
+        if (i < N) {
+            v = ids[i];
+            if (ids_copy) ids_copy[i] = v;
+            if (w_copy) w_copy[i] = w_in[i];
+        }
+        const bool valid = v >= 0 && v < E;
+        my_id[st] = v;
+        const int key = v & (MAX_E - 1);
+        uint64_t same = __ballot(valid);
+        if (!valid) same = ~same;
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const uint64_t bal = __ballot((key >> bit) & 1);
+            same &= ((key >> bit) & 1) ? bal : ~bal;
+        }
+        const int before = s_cnt[wave][key];
+        my_rank[st] = before + __popcll(same & lower);
+        if (valid && (same & lower) == 0ull) s_cnt[wave][key] = before + __popcll(same);
+    }
+    __syncthreads();
+    {
+        int run = 0;                                  // thread e: per-wave bases and the total of expert e
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const int c = s_cnt[w][tid];
+            s_cnt[w][tid] = run;
+            run += c;
+        }
+        s_off[tid] = (tid < E) ? run : 0;
+    }
+    __syncthreads();
+    for (int off = 1; off < MAX_E; off <<= 1) {       // inclusive scan over experts
+        const int add = (tid >= off) ? s_off[tid - off] : 0;
+        __syncthreads();
+        s_off[tid] += add;
+        __syncthreads();
+    }
+    if (tid < E) offsets[tid + 1] = s_off[tid];
+    if (tid == 0) offsets[0] = 0;
+#pragma unroll
+    for (int st = 0; st < PER_WAVE / 64; ++st) {
+        const int i = wave * PER_WAVE + st * 64 + lane;
+        if (i >= N) continue;
+        const int e = my_id[st];
+        if (e < 0 || e >= E) {
+            flags[0] = 1;
+            inv_perm[i] = -1;
+            continue;
+        }
+        const int pos = (e ? s_off[e - 1] : 0) + s_cnt[wave][e] + my_rank[st];
+        inv_perm[i] = pos;
+        perm[pos] = i;
+        row_token[pos] = i / k;
+    }
+}
+
 }  // namespace
 
 hipError_t launch_permute(moe_ctx* c, const int32_t* ids_in, int32_t* ids_copy, const float* w_in,
@@ -139,6 +218,11 @@ hipError_t launch_permute(moe_ctx* c, const int32_t* ids_in, int32_t* ids_copy, 
     const moe_dims& D = c->dims;
     const int N = D.T * D.k;
     const int n_chunks = (N + PERM_CHUNK - 1) / PERM_CHUNK;
+    if (n_chunks == 1) {
+        hipLaunchKernelGGL(permute_one_chunk, dim3(1), dim3(256), 0, c->stream, ids_in, N, D.E, ids_copy, w_in, w_copy,
+                           offsets, perm, inv_perm, c->row_token, D.k, c->flags);
+        return hipGetLastError();
+    }
     if (n_chunks > 0)
         hipLaunchKernelGGL(chunk_hist_rank, dim3(n_chunks), dim3(256), 0, c->stream, ids_in, N, D.E,
                            c->chunk_counts, inv_perm, ids_copy);
