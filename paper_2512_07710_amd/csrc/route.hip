@@ -5,9 +5,9 @@
 // the activations are bf16 already, every product x*w_plane is exact in fp32 and the
 // accumulated logit is as accurate as an fp32 FMA chain, at matrix-core speed.
 //
-// One block scores 128 tokens against all experts.  Wave w owns a quarter of the
+// One block scores 128, 64 or 32 tokens against all experts.  Wave w owns a quarter of the
 // (padded) experts: its weight operands come straight from global memory, fully
-// coalesced, while the 128-token activation tile is staged through LDS and shared by
+// coalesced, while the activation tile is staged through LDS and shared by
 // the four waves.  The product is taken as (experts x tokens), so a lane owns one
 // token column; each lane pair then extracts the k best of the wave's experts for its
 // token with register scans and one cross-half shuffle per round (larger score wins,
@@ -268,7 +268,7 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     __syncthreads();                                           // all reads of the activation stages are done
 
     if (IDS) {
-        // every lane looks up the logged ids of its four tokens among the experts it holds
+        // every lane looks up the logged ids of its TS tokens among the experts it holds
         float* sel = reinterpret_cast<float*>(smem);           // [RT][MAX_K] logits of the logged ids
         for (int i = tid; i < RT * MAX_K; i += 256) sel[i] = 0.f;   // ids outside [0,E) keep logit 0
         __syncthreads();
