@@ -157,10 +157,6 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                                                         uint8_t* __restrict__ hq, float* __restrict__ hs,
                                                         float* __restrict__ y_perm) {
     constexpr int FT = GATED ? 128 : 256;                      // output features per tile
-    // how the refill copies are placed inside a K step (see the pipeline note below): one behind each matrix
-    // instruction.  (In two bursts of four the gate/up projection misses the L2 a quarter less often, but
-    // runs 4 % slower.)
-    constexpr bool SPREAD = true;
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     // [3][256 weight rows][128 B] then [2][256 activation rows][128 B]: all 160 KiB.  The amax
     // exchange of the epilogue reuses the first bytes once the main loop is over.
@@ -258,10 +254,10 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     // kb (before sub-tile product 6 of 8).  Behind that barrier block kb+1 is complete in LDS and the
     // slots of block kb are free.  The copies that refill them follow: activation block kb+2, then
     // weight block kb+3 - always in that order, so that "all but the newest four copies have landed" is
-    // exactly "everything but the weight block two steps ahead".  SPREAD: they go out one behind each
-    // matrix instruction (activations over products 6 and 7, weights over products 0 and 1 of the next
-    // step), so that the wave does not sit at the issue of a copy while the queue drains; otherwise in
-    // two bursts of four at products 6 and 7.  Products 6 and 7 already fetch the first operands of
+    // exactly "everything but the weight block two steps ahead".  They go out one behind each matrix
+    // instruction (activations over products 6 and 7, weights over products 0 and 1 of the next step),
+    // so that the wave does not sit at the issue of a copy while the queue drains (in two bursts of four
+    // the gate/up projection ran 4 % slower).  Products 6 and 7 already fetch the first operands of
     // block kb+1 into registers.
     issue_x(0, 0);
     issue_w(0, 0);
@@ -381,11 +377,9 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                     for (int t2 = 0; t2 < 2; ++t2) asm volatile("v_mov_b32 %0, %1" : "=v"(xs_cur[t2]) : "v"(xs_n[t2]));
                 }
                 if (ts == 0) mfma_first(T0, a[s & 1][0], b[0][0]); else mfma_first(T1, a[s & 1][0], b[1][0]);
-                if (SPREAD) {
-                    // one copy behind every matrix instruction: weight block kb+2 over products 0 and 1
-                    if (i < 2 && kb >= 1 && kb + 2 < nkb) issue_w1(kb + 2, wprev, i * 2);
-                    if (i == 7 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 2);
-                }
+                // one copy behind every matrix instruction: weight block kb+2 over products 0 and 1
+                if (i < 2 && kb >= 1 && kb + 2 < nkb) issue_w1(kb + 2, wprev, i * 2);
+                if (i == 7 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 2);
                 if (ts == 0 && s < 3) {
 #pragma unroll
                     for (int ks = 0; ks < 2; ++ks)
@@ -397,16 +391,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
                     if (kb + 2 < nkb) {
                         xs_load(xs_n[0], kb + 2, 0);
                         xs_load(xs_n[1], kb + 2, 1);
-                        if (SPREAD) X_COPY(kb + 2, kb & 1, 0); else issue_x(kb + 2, kb & 1);
+                        X_COPY(kb + 2, kb & 1, 0);
                     }
                 }
-                if (!SPREAD && i == 7 && kb + 3 < nkb) issue_w(kb + 3, wslot);
                 if (ts == 0) mfma_acc(T0, a[s & 1][1], b[0][1]); else mfma_acc(T1, a[s & 1][1], b[1][1]);
-                if (SPREAD) {
-                    if (i < 2 && kb >= 1 && kb + 2 < nkb) issue_w1(kb + 2, wprev, i * 2 + 1);
-                    if (i == 6 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 1);
-                    if (i == 7 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 3);
-                }
+                if (i < 2 && kb >= 1 && kb + 2 < nkb) issue_w1(kb + 2, wprev, i * 2 + 1);
+                if (i == 6 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 1);
+                if (i == 7 && kb + 2 < nkb) X_COPY(kb + 2, kb & 1, 3);
                 if (i == 0) {
                     FOLD(3, 1, sc_pend);
                 } else {
