@@ -197,8 +197,8 @@ def test_config3_zipf_replay(gpu_lib):
 
 
 def test_config4_routed(gpu_lib):
-    _fullsize(gpu_lib, CONFIGS[4], "routed", n_tokens_e2e=32)
+    _fullsize(gpu_lib, CONFIGS[4], "routed", n_tokens_e2e=128)
 
 
 def test_config4_replay(gpu_lib):
-    _fullsize(gpu_lib, CONFIGS[4], "replay", n_tokens_e2e=32)
+    _fullsize(gpu_lib, CONFIGS[4], "replay", n_tokens_e2e=128)
