@@ -38,17 +38,17 @@ extern "C" {
 #define MOE_OK        0
 #define MOE_EINVAL   -1   /* null pointer, bad shape, d or F not a multiple of 128, k > E, block != 128 */
 #define MOE_EHIP     -2   /* a HIP runtime call or kernel launch failed */
-#define MOE_EBADIDS  -3   /* moe_check_ids found an expert id outside [0,E) */
+#define MOE_EBADIDS  -3   /* moe_check_ids found an expert id outside [0,E), or one repeated inside a token */
 #define MOE_ENOMEM   -4   /* workspace allocation failed */
 
 typedef struct moe_ctx moe_ctx;
 
 typedef struct {
-    int32_t T;  /* tokens per call (upper bound is not needed: exact) */
+    int32_t T;  /* tokens per call (upper bound is not needed: exact); T*k <= 2^30, T*d < 2^31 */
     int32_t d;  /* hidden size, multiple of 128 */
     int32_t E;  /* experts, 1..256 */
     int32_t k;  /* experts per token, 1..min(E,16) */
-    int32_t F;  /* expert FFN width, multiple of 128 */
+    int32_t F;  /* expert FFN width, multiple of 128; F*d < 2^32 */
 } moe_dims;
 
 /* Create a context for one layer shape.  Allocates the internal device workspace
@@ -80,7 +80,9 @@ int moe_route(moe_ctx* ctx, const uint16_t* x_bf16, const float* W_router, const
  * expert id: offsets[e] = number of assignments with id < e, offsets[E] = N;
  * inv_perm[i] = offsets[id_i] + #{i' < i : id_i' = id_i}; perm[inv_perm[i]] = i.
  * Ids outside [0,E) never fault; their assignments are skipped and a device flag
- * is raised that moe_check_ids reports. */
+ * is raised that moe_check_ids reports.  An id that repeats an earlier slot of the same
+ * token raises a second flag (also reported by moe_check_ids); the permutation is still the
+ * stable sort of the ids as given. */
 int moe_route_replay(moe_ctx* ctx, const uint16_t* x_bf16, const int32_t* logged_idx,
                      const float* logged_w, int32_t* topk_idx, float* topk_w,
                      int32_t* offsets, int32_t* perm, int32_t* inv_perm);
@@ -97,7 +99,8 @@ int moe_route_replay_ids(moe_ctx* ctx, const uint16_t* x_bf16, const float* W_ro
                          int32_t* offsets, int32_t* perm, int32_t* inv_perm);
 
 /* Synchronises the stream and returns MOE_EBADIDS if any routing call on this
- * context since the last check met an expert id outside [0,E), else MOE_OK. */
+ * context since the last check met an expert id outside [0,E), or (replay calls) a
+ * logged id that occurs twice inside one token; else MOE_OK.  Clears both flags. */
 int moe_check_ids(moe_ctx* ctx);
 
 /* Per-row FP8 quantisation with optional fan-out to expert order.
@@ -133,7 +136,8 @@ int moe_quantize_weights_fp8(moe_ctx* ctx, const uint16_t* w_bf16, int64_t rows,
  *   xq [rows,K] u8 and xs [K/128][rows] f32 as written by moe_quantize_fp8 (dst_rows = NULL);
  *   Wq [NOUT,K] u8; ws [NOUT/128, K/128] f32; y [rows,NOUT] f32.  K and NOUT multiples of 128.
  * Uses the context's work-list storage: ceil(rows/256)*ceil(NOUT/256) must not exceed
- * (T*k/256 + E) * (F/128 + ceil(d/256)) of the context's dims, else MOE_EINVAL. */
+ * (T*k/256 + E) * (F/128 + ceil(d/256)) of the context's dims, else MOE_EINVAL; NOUT*K must be
+ * below 2^32 (MOE_EINVAL otherwise). */
 int moe_linear_fp8(moe_ctx* ctx, const uint8_t* xq, const float* xs, int32_t rows, int32_t K,
                    const uint8_t* Wq, const float* ws, int32_t NOUT, float* y);
 
@@ -157,11 +161,12 @@ int moe_expert_ffn_fp8(moe_ctx* ctx, const uint8_t* xq_perm, const float* xs_per
 
 /* The same FFN with the token gather fused into the gate/up GEMM: xq_tok [T,d] u8 and xs_tok [d/128][T] f32
  * are the activations quantised ONCE per token, in token order (moe_quantize_fp8 with dst_rows = NULL);
- * expert-sorted row p reads token perm[p]/k through the row -> token map that the last moe_route,
- * moe_route_replay or moe_route_replay_ids call on this context left in its workspace.  No expert-ordered
- * copy of the activations exists: the layer saves its k-fold write and re-read.  Results are bit-identical
- * to moe_expert_ffn_fp8 on the gathered rows.  offsets must be the ones that routing call produced. */
-int moe_expert_ffn_fp8_gather(moe_ctx* ctx, const uint8_t* xq_tok, const float* xs_tok,
+ * expert-sorted row p reads token perm[p]/k.  perm [N] i32 and offsets [E+1] i32 are the ones a routing call
+ * wrote for this batch; the call keeps no routing state of its own.  A perm entry that names a token
+ * beyond T-1 reads token T-1 instead of faulting.  No expert-ordered copy of the activations exists: the
+ * layer saves its k-fold write and re-read.  Results are bit-identical to moe_expert_ffn_fp8 on the
+ * gathered rows. */
+int moe_expert_ffn_fp8_gather(moe_ctx* ctx, const uint8_t* xq_tok, const float* xs_tok, const int32_t* perm,
                               const int32_t* offsets, const uint8_t* W1, const uint8_t* W3,
                               const uint8_t* W2, const float* s1, const float* s3, const float* s2,
                               float* y_perm);
@@ -172,24 +177,6 @@ int moe_expert_ffn_fp8_gather(moe_ctx* ctx, const uint8_t* xq_tok, const float* 
  *   y_perm [N,d] f32; inv_perm [N] i32; topk_w [T,k] f32; y_bf16 [T,d]. */
 int moe_combine(moe_ctx* ctx, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
                 uint16_t* y_bf16);
-
-/* 16-bit storage of the expert outputs between the down projection and the combine (an
- * implementation format of this library; the paper does not fix the precision of that
- * intermediate, fp32 y_perm above is the reference form).  Same computation as
- * moe_expert_ffn_fp8_gather, but row p of the result leaves as
- *   ys[p, g] = amax_g / 32767 with amax_g = max |y_perm[p, 128g .. 128g+127]|   (1 if all zero), fp32,
- *   yq[p, c] = round-half-even(y_perm[p, c] * (32767 / amax_g)) as int16, product and quotient in fp32,
- * yq [N, d] and ys [N, d/128] row-major, device pointers owned by the caller: half the bytes of
- * fp32 rows for a relative error of about 2^-16 of each group's maximum, far inside the layer's
- * 2e-3 budget.  moe_combine_i16 is moe_combine over such rows:
- *   y[t, c] = bf16( sum_j (topk_w[t, j] * ys[r_j, c/128]) * yq[r_j, c] ),  r_j = inv_perm[t*k + j],
- * fp32 multiply-adds in slot order.  Errors as for the fp32 calls. */
-int moe_expert_ffn_fp8_gather_i16(moe_ctx* ctx, const uint8_t* xq_tok, const float* xs_tok,
-                                  const int32_t* offsets, const uint8_t* W1, const uint8_t* W3,
-                                  const uint8_t* W2, const float* s1, const float* s3, const float* s2,
-                                  int16_t* yq, float* ys);
-int moe_combine_i16(moe_ctx* ctx, const int16_t* yq, const float* ys, const int32_t* inv_perm,
-                    const float* topk_w, uint16_t* y_bf16);
 
 /* Length-based load balancing before rollout (paper section 3.1.1): distributes n samples over
  * n_groups worker groups so that the groups' total predicted generation lengths are about equal.
@@ -207,10 +194,22 @@ int moe_combine_i16(moe_ctx* ctx, const int16_t* yq, const float* ys, const int3
 int moe_balance_lengths(const int64_t* pred_len, int64_t n, int32_t n_groups, int32_t equal_count,
                         int32_t* group_of, int64_t* order, int64_t* bounds, int64_t* totals);
 
-/* Device pointers to the hidden activations written by the last
- * moe_expert_ffn_fp8 call (hq [N,F] u8, hs [F/128][N] f32, group-major); valid until the
- * context is destroyed.  For stage-isolated checks. */
-int moe_debug_hidden(moe_ctx* ctx, const uint8_t** hq, const float** hs);
+/* Copies the hidden activations written by the last expert-FFN call on this context into
+ * caller-owned device buffers: hq_out [N,F] u8, hs_out [F/128][N] f32 (group-major).  Enqueued on the
+ * context's stream.  For stage-isolated checks. */
+int moe_debug_copy_hidden(moe_ctx* ctx, uint8_t* hq_out, float* hs_out);
+
+/* Measured ceilings for benchmarks (neither is part of the layer; both enqueue on the context's stream).
+ * moe_probe_copy: a plain streaming device copy of `bytes` bytes (multiple of 16) from src to dst, both
+ *   device pointers owned by the caller: 2*bytes / its duration is what HBM delivers to a kernel that
+ *   does nothing else.
+ * moe_probe_fp8_mfma: `blocks` workgroups of 8 waves run `steps` times the matrix work one wave of the grouped
+ *   GEMM does per 128-wide K block (8 sub-tile products of two 32x32x64 FP8 matrix instructions, random operand
+ *   bits held in registers: no LDS, no memory), scaled != 0: each product folded into its accumulator with 16
+ *   fp32 multiply-adds as per-block scaling requires.  FLOP = blocks * 8 waves * steps * 16 * 2*32*32*64.
+ *   sink: one float of device memory (practically never written). */
+int moe_probe_copy(moe_ctx* ctx, const void* src, void* dst, int64_t bytes);
+int moe_probe_fp8_mfma(moe_ctx* ctx, int32_t blocks, int32_t steps, int32_t scaled, float* sink);
 
 /* Kernel timing for benchmarks.  While enabled, moe_expert_ffn_fp8 brackets its two
  * GEMM kernels with HIP events on the context's stream (at most 512 calls are kept

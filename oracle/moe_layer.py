@@ -23,8 +23,6 @@ standard definitions below are the reading taken):
            (activation scale x weight block scale); h = silu(g)*u; h is
            quantised like x; y_perm = hq W2^T, same rescaling.
   combine  y[t] = sum_j w[t,j] * y_perm[row of (t,j)], rounded to bf16 once.
-  i16      optional 16-bit block-scaled storage of y_perm (quantize_rows_i16): an implementation
-           format between the down projection and the combine, not part of the paper's method.
 
 All arithmetic is float64 except the rounding points named above.
 """
@@ -146,34 +144,6 @@ def quantize_blocks(w: np.ndarray):
             codes[bi * G:(bi + 1) * G, bj * G:(bj + 1) * G] = e4m3_encode(r.astype(np.float64))
             scales[bi, bj] = s
     return codes, scales
-
-
-def quantize_rows_i16(y: np.ndarray):
-    """16-bit block-scaled storage of the expert outputs between the down projection and the combine (an
-    implementation format of this library, not the paper's: the paper is silent on the precision of that
-    intermediate; plain fp32 is the reference form).
-
-    y [R,C] float64 holding fp32-representable values, C a multiple of 128.  Per row and 128 contiguous
-    columns: s = fp32(amax/32767) is the stored scale and q = fp32(32767/amax) the multiplier (both 1 if the
-    group is all zero); code = round-half-even(fp32(y*q)) as int16.  (A multiplier, not a division by s: the
-    format is this library's own, and one reciprocal per group keeps the kernel's epilogue short.)
-    Returns codes i16 [R,C] and scales f32 [R, C/128].  |y - s*code| <= s/2 up to a few fp32 roundings.
-    """
-    R, C = y.shape
-    assert C % G == 0
-    yg = y.reshape(R, C // G, G)
-    amax = np.abs(yg).max(axis=2)
-    safe = np.where(amax == 0, 1.0, amax)
-    s = np.where(amax == 0, 1.0, amax / 32767.0).astype(np.float32)
-    q = np.where(amax == 0, 1.0, 32767.0 / safe).astype(np.float32)
-    r = (yg * q.astype(np.float64)[:, :, None]).astype(np.float32)
-    codes = np.rint(r.astype(np.float64)).astype(np.int16)      # numpy's rint rounds half to even
-    return codes.reshape(R, C), s
-
-
-def dequantize_rows_i16(codes: np.ndarray, scales: np.ndarray) -> np.ndarray:
-    """float64 value of every code: scale of its (row, 128-column group) times the code."""
-    return codes.astype(np.float64) * np.repeat(scales.astype(np.float64), G, axis=1)
 
 
 def gather_quantize(x_bits: np.ndarray, perm: np.ndarray, k: int):

@@ -19,8 +19,8 @@ _lib: Optional[ctypes.CDLL] = None
 
 EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_route_replay_ids",
            "moe_check_ids", "moe_quantize_fp8", "moe_quantize_weights_fp8", "moe_linear_fp8", "moe_expert_ffn_fp8",
-           "moe_expert_ffn_fp8_gather",
-           "moe_expert_ffn_fp8_gather_i16", "moe_combine", "moe_combine_i16", "moe_balance_lengths", "moe_debug_hidden", "moe_profile_enable", "moe_profile_read", "moe_version")
+           "moe_expert_ffn_fp8_gather", "moe_combine", "moe_balance_lengths", "moe_debug_copy_hidden",
+           "moe_probe_copy", "moe_probe_fp8_mfma", "moe_profile_enable", "moe_profile_read", "moe_version")
 
 
 class MoEError(RuntimeError):
@@ -56,12 +56,12 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_linear_fp8.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
     lib.moe_quantize_fp8.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp]
     lib.moe_expert_ffn_fp8.argtypes = [vp] * 11
-    lib.moe_expert_ffn_fp8_gather.argtypes = [vp] * 11
-    lib.moe_expert_ffn_fp8_gather_i16.argtypes = [vp] * 12
+    lib.moe_expert_ffn_fp8_gather.argtypes = [vp] * 12
     lib.moe_combine.argtypes = [vp] * 5
-    lib.moe_combine_i16.argtypes = [vp] * 6
     lib.moe_balance_lengths.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
-    lib.moe_debug_hidden.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp)]
+    lib.moe_debug_copy_hidden.argtypes = [vp, vp, vp]
+    lib.moe_probe_copy.argtypes = [vp, vp, vp, i64]
+    lib.moe_probe_fp8_mfma.argtypes = [vp, i32, i32, i32, vp]
     lib.moe_profile_enable.argtypes = [vp, i32]
     lib.moe_profile_read.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(i32)]
     for name in EXPORTS:
@@ -158,27 +158,13 @@ def moe_expert_ffn_fp8(ctx, xq_perm, xs_perm, offsets, W1, W3, W2, s1, s3, s2, y
                                              _ptr(y_perm, f32)), "moe_expert_ffn_fp8")
 
 
-def moe_expert_ffn_fp8_gather(ctx, xq_tok, xs_tok, offsets, W1, W3, W2, s1, s3, s2, y_perm) -> None:
+def moe_expert_ffn_fp8_gather(ctx, xq_tok, xs_tok, perm, offsets, W1, W3, W2, s1, s3, s2, y_perm) -> None:
     u8, f32 = torch.uint8, torch.float32
     _check(load_library().moe_expert_ffn_fp8_gather(ctx, _ptr(xq_tok, u8), _ptr(xs_tok, f32),
+                                                    _ptr(perm, torch.int32),
                                                     _ptr(offsets, torch.int32), _ptr(W1, u8), _ptr(W3, u8),
                                                     _ptr(W2, u8), _ptr(s1, f32), _ptr(s3, f32), _ptr(s2, f32),
                                                     _ptr(y_perm, f32)), "moe_expert_ffn_fp8_gather")
-
-
-def moe_expert_ffn_fp8_gather_i16(ctx, xq_tok, xs_tok, offsets, W1, W3, W2, s1, s3, s2, yq, ys) -> None:
-    u8, f32 = torch.uint8, torch.float32
-    _check(load_library().moe_expert_ffn_fp8_gather_i16(ctx, _ptr(xq_tok, u8), _ptr(xs_tok, f32),
-                                                        _ptr(offsets, torch.int32), _ptr(W1, u8), _ptr(W3, u8),
-                                                        _ptr(W2, u8), _ptr(s1, f32), _ptr(s3, f32), _ptr(s2, f32),
-                                                        _ptr(yq, torch.int16), _ptr(ys, f32)),
-           "moe_expert_ffn_fp8_gather_i16")
-
-
-def moe_combine_i16(ctx, yq, ys, inv_perm, topk_w, y) -> None:
-    _check(load_library().moe_combine_i16(ctx, _ptr(yq, torch.int16), _ptr(ys, torch.float32),
-                                          _ptr(inv_perm, torch.int32), _ptr(topk_w, torch.float32),
-                                          _ptr(y, torch.bfloat16)), "moe_combine_i16")
 
 
 def moe_combine(ctx, y_perm, inv_perm, topk_w, y) -> None:
@@ -204,11 +190,18 @@ def moe_balance_lengths(pred_len, n_groups: int, equal_count: bool = True):
     return group_of, order, bounds, totals
 
 
-def moe_debug_hidden(ctx):
-    """Raw device addresses (hq, hs) of the hidden activations kept in the context."""
-    a, b = ctypes.c_void_p(), ctypes.c_void_p()
-    _check(load_library().moe_debug_hidden(ctx, ctypes.byref(a), ctypes.byref(b)), "moe_debug_hidden")
-    return a.value, b.value
+def moe_debug_copy_hidden(ctx, hq_out, hs_out) -> None:
+    _check(load_library().moe_debug_copy_hidden(ctx, _ptr(hq_out, torch.uint8), _ptr(hs_out, torch.float32)),
+           "moe_debug_copy_hidden")
+
+
+def moe_probe_copy(ctx, src, dst, nbytes: int) -> None:
+    _check(load_library().moe_probe_copy(ctx, _ptr(src), _ptr(dst), nbytes), "moe_probe_copy")
+
+
+def moe_probe_fp8_mfma(ctx, blocks: int, steps: int, scaled: bool, sink) -> None:
+    _check(load_library().moe_probe_fp8_mfma(ctx, blocks, steps, 1 if scaled else 0, _ptr(sink, torch.float32)),
+           "moe_probe_fp8_mfma")
 
 
 def moe_profile_enable(ctx, on: bool) -> None:

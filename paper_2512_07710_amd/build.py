@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libmoe355.so")
-SOURCES = ("moe_api.hip", "route.hip", "permute.hip", "quantize.hip", "wquant.hip", "ffn.hip", "combine.hip", "balance.hip")
+SOURCES = ("moe_api.hip", "route.hip", "permute.hip", "quantize.hip", "wquant.hip", "ffn.hip", "combine.hip", "balance.hip", "probe.hip")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 code generation is switched off for every device compile
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",

@@ -76,86 +76,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
     (void)T;
 }
 
-// The same gather over 16-bit rows: row value = scale of its (row, 128-column group) x code.  One thread per
-// 8 columns; w * scale is formed once per slot and column group, then one multiply-add per element in slot order.
-template <int KT>
-__global__ __launch_bounds__(256) void combine_i16_kernel(const int16_t* __restrict__ yq, const float* __restrict__ ys,
-                                                          const int32_t* __restrict__ inv_perm,
-                                                          const float* __restrict__ topk_w, int T, int d, int k_rt,
-                                                          uint16_t* __restrict__ y) {
-    __shared__ int32_t s_row[MAX_K];
-    __shared__ float s_w[MAX_K];
-    const int k = KT > 0 ? KT : k_rt;
-    const int t = blockIdx.x;
-    if (threadIdx.x < k) {
-        s_row[threadIdx.x] = inv_perm[(size_t)t * k + threadIdx.x];
-        s_w[threadIdx.x] = topk_w[(size_t)t * k + threadIdx.x];
-    }
-    __syncthreads();
-    const int nb = d / QBLOCK;
-    constexpr int KU = KT > 0 ? KT : 1;
-    for (int c8 = threadIdx.x; c8 < d / 8; c8 += 256) {
-        float acc[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) acc[i] = 0.f;
-        auto add = [&](const uint4& v, float f) {
-            const uint32_t w4[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                acc[2 * i] = fmaf(f, (float)(int16_t)(w4[i] & 0xFFFFu), acc[2 * i]);
-                acc[2 * i + 1] = fmaf(f, (float)(int16_t)(w4[i] >> 16), acc[2 * i + 1]);
-            }
-        };
-        if (KT > 0) {
-            uint4 v[KU];
-            float f[KU];
-#pragma unroll
-            for (int j = 0; j < KU; ++j) {
-                const int row = s_row[j];
-                if (row < 0) { v[j] = make_uint4(0u, 0u, 0u, 0u); f[j] = 0.f; continue; }   // invalid expert id: adds nothing
-                v[j] = *reinterpret_cast<const uint4*>(yq + (size_t)row * d + (size_t)c8 * 8);
-                f[j] = s_w[j] * ys[(size_t)row * nb + (c8 >> 4)];
-            }
-#pragma unroll
-            for (int j = 0; j < KU; ++j)
-                if (s_row[j] >= 0) add(v[j], f[j]);
-        } else {
-            for (int j = 0; j < k; ++j) {
-                const int row = s_row[j];
-                if (row < 0) continue;
-                const uint4 v = *reinterpret_cast<const uint4*>(yq + (size_t)row * d + (size_t)c8 * 8);
-                add(v, s_w[j] * ys[(size_t)row * nb + (c8 >> 4)]);
-            }
-        }
-        uint4 o;
-        o.x = f32_to_bf16_rne(acc[0]) | (f32_to_bf16_rne(acc[1]) << 16);
-        o.y = f32_to_bf16_rne(acc[2]) | (f32_to_bf16_rne(acc[3]) << 16);
-        o.z = f32_to_bf16_rne(acc[4]) | (f32_to_bf16_rne(acc[5]) << 16);
-        o.w = f32_to_bf16_rne(acc[6]) | (f32_to_bf16_rne(acc[7]) << 16);
-        *reinterpret_cast<uint4*>(y + (size_t)t * d + (size_t)c8 * 8) = o;
-    }
-    (void)T;
-}
-
 }  // namespace
-
-hipError_t launch_combine_i16(moe_ctx* c, const int16_t* yq, const float* ys, const int32_t* inv_perm,
-                              const float* topk_w, uint16_t* y) {
-    const moe_dims& D = c->dims;
-#define MOE_COMBINE_I16(KT_)                                                                                  \
-    hipLaunchKernelGGL(combine_i16_kernel<KT_>, dim3(D.T), dim3(256), 0, c->stream, yq, ys, inv_perm, topk_w,  \
-                       D.T, D.d, D.k, y)
-    switch (D.k) {
-        case 1: MOE_COMBINE_I16(1); break;
-        case 2: MOE_COMBINE_I16(2); break;
-        case 4: MOE_COMBINE_I16(4); break;
-        case 6: MOE_COMBINE_I16(6); break;
-        case 8: MOE_COMBINE_I16(8); break;
-        default: MOE_COMBINE_I16(0); break;
-    }
-#undef MOE_COMBINE_I16
-    return hipGetLastError();
-}
 
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
                           uint16_t* y) {

@@ -25,9 +25,8 @@
 //
 // GEMM1: staged rows of wave wf are [64 gate rows | 64 up rows] of the same features;
 //        epilogue h = silu(g)*u, re-quantised to e4m3 with one scale per (row, 128 features).
-// GEMM2: staged rows are 256 consecutive output features; epilogue: fp32 rows (or 16-bit codes with one
-//        scale per row and 128 features), turned through LDS so that every row is stored in contiguous
-//        256-byte pieces.
+// GEMM2: staged rows are 256 consecutive output features; epilogue: fp32 rows, turned through LDS so
+//        that every row is stored in contiguous 256-byte pieces.
 #include "moe_internal.hpp"
 
 namespace moe355 {
@@ -137,16 +136,15 @@ __device__ inline v8i lds_operand(const uint8_t* row, uint32_t o0, uint32_t o1) 
 // GATED = true : Wa = W1, Wb = W3 [E, NOUT, K]; feature tile = 128 features (gate + up rows)
 // GATED = false: Wa = W2 [E, NOUT, K]; feature tile = 256 output features
 // act [N, K] u8 are the expert-sorted activations; act_s [K/128][N] f32 their scales, K-block major.
-// GATHER (gate/up only): act [T, K] is in TOKEN order and sorted row p reads the codes of token
-// row_token[p]: the expert-ordered copy of the codes is never materialised.  The scales act_s
+// GATHER (gate/up only): act [n_tok, K] is in TOKEN order and sorted row p reads the codes of token
+// perm[p] / fan (clamped to the last token, so that a foreign perm cannot address outside act): the
+// expert-ordered copy of the codes is never materialised.  The scales act_s
 // [K/128][n_rows] are in sorted order in both cases (they are 1/128 of the data; a lane-scattered
 // scale read per K step would cost more than it saves).
-// Q16 (down projection only): the output goes out as 16-bit codes with one fp32 scale per row and 128 columns
-// (s = amax / 32767, code = round(y * (32767 / amax))), through the hq / hs arguments, instead of fp32 rows.
-template <bool GATED, bool GATHER, bool Q16 = false>
+template <bool GATED, bool GATHER>
 __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restrict__ act,
                                                         const float* __restrict__ act_s, int n_rows,
-                                                        const int32_t* __restrict__ row_token,
+                                                        const int32_t* __restrict__ perm, int fan, int n_tok,
                                                         const int32_t* __restrict__ offsets,
                                                         const Work* __restrict__ work,
                                                         const int32_t* __restrict__ n_work,
@@ -199,7 +197,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
             f = min(f, NOUT - 1);
             w_off[j] = (uint32_t)f * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
             const int p = min(wk.row0 + r, row_end - 1);      // rows past the tile repeat its last row
-            const int src = GATHER ? row_token[p] : p - wk.row0;
+            const int src = GATHER ? (int)min((uint32_t)perm[p] / (uint32_t)fan, (uint32_t)(n_tok - 1)) : p - wk.row0;
             x_off[j] = (uint32_t)src * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
         }
     }
@@ -495,50 +493,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
         // pipeline would take as 64 separate requests.  Each wave therefore turns its 128 x 64 block through a
         // private LDS region (the operand rings are free now), 64 features at a time, and writes 256 contiguous
         // bytes of a row with every 16 lanes.
-        if (Q16) {
-            // Same turn through LDS with 16-bit codes: the wave's 128 features are exactly one scale group, whose
-            // amax is a lane-local maximum and one exchange between the two lanes that share a token.
-            if (wave_active && f0 + wf * 128 < NOUT) {
-                constexpr int Q_STRIDE = 272;                  // bytes per staged token row: 128 codes + 16 of padding
-                uint8_t* const stage = smem + wave * (64 * Q_STRIDE);
-                int16_t* const yq = reinterpret_cast<int16_t*>(hq);
-                const int blk = (f0 + wf * 128) / QBLOCK;
-#pragma unroll
-                for (int ts = 0; ts < 2; ++ts) {
-                    float am = 0.f;
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) am = fmaxf(am, fabsf(acc[s][ts][r]));
-                    am = fmaxf(am, __shfl_xor(am, 32));
-                    const float sc = (am == 0.f) ? 1.0f : am / 32767.0f;      // stored scale
-                    const float mul = (am == 0.f) ? 1.0f : 32767.0f / am;     // the format's multiplier: one division per group
-                    uint8_t* srow = stage + (ts * 32 + l32) * Q_STRIDE + half * 8;
-#pragma unroll
-                    for (int s = 0; s < 4; ++s)
-#pragma unroll
-                        for (int r4 = 0; r4 < 4; ++r4) {
-                            const int c0 = (int)rintf(acc[s][ts][r4 * 4] * mul), c1 = (int)rintf(acc[s][ts][r4 * 4 + 1] * mul);
-                            const int c2 = (int)rintf(acc[s][ts][r4 * 4 + 2] * mul), c3 = (int)rintf(acc[s][ts][r4 * 4 + 3] * mul);
-                            uint2 v;
-                            v.x = ((uint32_t)c0 & 0xFFFFu) | ((uint32_t)c1 << 16);
-                            v.y = ((uint32_t)c2 & 0xFFFFu) | ((uint32_t)c3 << 16);
-                            *reinterpret_cast<uint2*>(srow + (s * 32 + r4 * 8) * 2) = v;
-                        }
-                    const int p = wk.row0 + wt * 64 + ts * 32 + l32;
-                    if (p < row_end && half == 0) hs[(size_t)p * nblk_out + blk] = sc;
-                }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#pragma unroll 4
-                for (int it = 0; it < 16; ++it) {
-                    const int trow = it * 4 + (lane >> 4);
-                    const uint4 v = *reinterpret_cast<const uint4*>(stage + trow * Q_STRIDE + (lane & 15) * 16);
-                    const int p = wk.row0 + wt * 64 + trow;
-                    if (p < row_end)
-                        *reinterpret_cast<uint4*>(yq + (size_t)p * NOUT + f0 + wf * 128 + (lane & 15) * 8) = v;
-                }
-            }
-        } else if (wave_active) {
+        if (wave_active) {
             constexpr int TS_STRIDE = 68;                      // floats per staged token row: 64 + 4 of padding
             float* const stage = reinterpret_cast<float*>(smem) + wave * (64 * TS_STRIDE);
 #pragma unroll
@@ -584,10 +539,9 @@ size_t ffn_work_bytes(int max_tiles, int F, int d) {
 static hipError_t set_lds_limits() {
     static bool attr_set = false;
     if (attr_set) return hipSuccess;
-    const void* kernels[4] = {reinterpret_cast<const void*>(&ffn_gemm<true, false>),
+    const void* kernels[3] = {reinterpret_cast<const void*>(&ffn_gemm<true, false>),
                               reinterpret_cast<const void*>(&ffn_gemm<true, true>),
-                              reinterpret_cast<const void*>(&ffn_gemm<false, false>),
-                              reinterpret_cast<const void*>(&ffn_gemm<false, false, true>)};
+                              reinterpret_cast<const void*>(&ffn_gemm<false, false>)};
     for (const void* k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)SMEM_BYTES);
         if (e != hipSuccess) return e;
@@ -596,22 +550,22 @@ static hipError_t set_lds_limits() {
     return hipSuccess;
 }
 
-// scales of the expert-sorted rows from the per-token scales: out[g][p] = in[g][row_token[p]]
-__global__ __launch_bounds__(256) void gather_scales(const float* __restrict__ in, int T, const int32_t* __restrict__ row_token,
-                                                     int N, float* __restrict__ out) {
+// scales of the expert-sorted rows from the per-token scales: out[g][p] = in[g][perm[p] / fan]
+__global__ __launch_bounds__(256) void gather_scales(const float* __restrict__ in, int T, const int32_t* __restrict__ perm,
+                                                     int fan, int N, float* __restrict__ out) {
     const int p = blockIdx.x * 256 + threadIdx.x;
     if (p >= N) return;
     const size_t g = blockIdx.y;
-    out[g * N + p] = in[g * T + row_token[p]];
+    const uint32_t t = min((uint32_t)perm[p] / (uint32_t)fan, (uint32_t)(T - 1));
+    out[g * N + p] = in[g * T + t];
 }
 
-// gathered == false: xq/xs are the expert-ordered activations [N,d], [d/128][N].
-// gathered == true : xq/xs are in token order [T,d], [d/128][T]; sorted row p reads token c->row_token[p]
-//                    (the scales are first brought into sorted order in the context's workspace).
-// yq != nullptr    : the down projection writes 16-bit codes yq [N,d] and scales ys [N][d/128] instead of y_perm.
-hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, bool gathered, const int32_t* offsets,
+// perm == nullptr: xq/xs are the expert-ordered activations [N,d], [d/128][N].
+// perm != nullptr: xq/xs are in token order [T,d], [d/128][T]; sorted row p reads token perm[p] / k
+//                  (the scales are first brought into sorted order in the context's workspace).
+hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, const int32_t* perm, const int32_t* offsets,
                              const uint8_t* W1, const uint8_t* W3, const uint8_t* W2, const float* s1,
-                             const float* s3, const float* s2, float* y_perm, int16_t* yq, float* ys) {
+                             const float* s3, const float* s2, float* y_perm) {
     const moe_dims& D = c->dims;
     hipError_t ea = set_lds_limits();
     if (ea != hipSuccess) return ea;
@@ -628,29 +582,22 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, boo
                        c->n_tiles);
     if (ev) (void)hipEventRecord(ev[0], c->stream);
     const int grid1 = ((c->max_tiles * nft1 + NXCD - 1) / NXCD) * NXCD;
-    if (gathered) {
+    if (perm) {
         hipLaunchKernelGGL(gather_scales, dim3((N + 255) / 256, D.d / QBLOCK), dim3(256), 0, c->stream, xs, D.T,
-                           c->row_token, N, c->xs_sorted);
+                           perm, D.k, N, c->xs_sorted);
         hipLaunchKernelGGL((ffn_gemm<true, true>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, c->xs_sorted, N,
-                           c->row_token, offsets, work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq, c->hs,
+                           perm, D.k, D.T, offsets, work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq, c->hs,
                            (float*)nullptr);
     } else {
         hipLaunchKernelGGL((ffn_gemm<true, false>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, N,
-                           (const int32_t*)nullptr, offsets, work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq,
+                           (const int32_t*)nullptr, 1, 1, offsets, work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq,
                            c->hs, (float*)nullptr);
     }
     if (ev) (void)hipEventRecord(ev[1], c->stream);
     const int grid2 = ((c->max_tiles * nft2 + NXCD - 1) / NXCD) * NXCD;
-    if (yq) {
-        // 16-bit output: codes and scales travel through the kernel's hq / hs arguments
-        hipLaunchKernelGGL((ffn_gemm<false, false, true>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq,
-                           c->hs, N, (const int32_t*)nullptr, offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2,
-                           (const float*)nullptr, D.F, D.d, reinterpret_cast<uint8_t*>(yq), ys, (float*)nullptr);
-    } else {
-        hipLaunchKernelGGL((ffn_gemm<false, false>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq, c->hs,
-                           N, (const int32_t*)nullptr, offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2,
-                           (const float*)nullptr, D.F, D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
-    }
+    hipLaunchKernelGGL((ffn_gemm<false, false>), dim3(grid2), dim3(NTHREADS), SMEM_BYTES, c->stream, c->hq, c->hs,
+                       N, (const int32_t*)nullptr, 1, 1, offsets, work2, n_work2, W2, (const uint8_t*)nullptr, s2,
+                       (const float*)nullptr, D.F, D.d, (uint8_t*)nullptr, (float*)nullptr, y_perm);
     if (ev) (void)hipEventRecord(ev[2], c->stream);
     return hipGetLastError();
 }
@@ -674,7 +621,7 @@ hipError_t launch_linear(moe_ctx* c, const uint8_t* xq, const float* xs, int32_t
     const int tiles = (rows + TOK_TILE - 1) / TOK_TILE;
     const int grid = ((tiles * nft + NXCD - 1) / NXCD) * NXCD;
     hipLaunchKernelGGL((ffn_gemm<false, false>), dim3(grid), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, xs, rows,
-                       (const int32_t*)nullptr, range, work, n_work, Wq, (const uint8_t*)nullptr, ws, (const float*)nullptr, K, NOUT, (uint8_t*)nullptr,
+                       (const int32_t*)nullptr, 1, 1, range, work, n_work, Wq, (const uint8_t*)nullptr, ws, (const float*)nullptr, K, NOUT, (uint8_t*)nullptr,
                        (float*)nullptr, y);
     return hipGetLastError();
 }

@@ -6,7 +6,10 @@
 //      among earlier equal ids of the chunk.
 //   2. scan_chunks: one block turns the per-chunk histograms into exclusive prefix
 //      sums over chunks (per expert) and the expert totals into offsets[0..E].
-//   3. scatter: position = offsets[e] + prefix[chunk][e] + rank; writes perm/inv_perm.
+//   3. scatter: position = offsets[e] + prefix[chunk][e] + rank; writes perm/inv_perm.  Ids that come
+//      from a log are also checked here: an id outside [0,E) raises flags[0], an id that repeats an
+//      earlier slot of the same token raises flags[1] (the permutation is still the stable sort of
+//      what was given).
 // The result is unique (stable), so it can be compared bit for bit.  Batches of at most PERM_CHUNK
 // assignments take one fused launch instead (permute_one_chunk).
 #include "moe_internal.hpp"
@@ -116,7 +119,7 @@ __global__ __launch_bounds__(256) void scatter(const int32_t* __restrict__ ids, 
                                                const int32_t* __restrict__ offsets,
                                                const float* __restrict__ w_in, float* __restrict__ w_copy,
                                                int32_t* __restrict__ perm, int32_t* __restrict__ inv_perm,
-                                               int32_t* __restrict__ row_token, int k, int32_t* __restrict__ flags) {
+                                               int k, bool check_dups, int32_t* __restrict__ flags) {
     const int i = blockIdx.x * 256 + threadIdx.x;
     if (i >= N) return;
     if (w_copy) w_copy[i] = w_in[i];
@@ -126,11 +129,16 @@ __global__ __launch_bounds__(256) void scatter(const int32_t* __restrict__ ids, 
         inv_perm[i] = -1;
         return;
     }
+    if (check_dups) {
+        const int first = i - i % k;                    // slot 0 of this assignment's token
+        bool dup = false;
+        for (int q = first; q < i; ++q) dup |= ids[q] == e;
+        if (dup) flags[1] = 1;
+    }
     const int chunk = i / PERM_CHUNK;
     const int pos = offsets[e] + chunk_prefix[(size_t)chunk * E + e] + inv_perm[i];   // inv_perm holds the rank
     inv_perm[i] = pos;
     perm[pos] = i;
-    row_token[pos] = i / k;                             // read by the gathering gate/up GEMM
 }
 
 // N <= PERM_CHUNK: the three steps in one block and one launch (decode-sized batches, where the launches
@@ -140,8 +148,7 @@ __global__ __launch_bounds__(256) void permute_one_chunk(const int32_t* __restri
                                                          int32_t* __restrict__ ids_copy,
                                                          const float* __restrict__ w_in, float* __restrict__ w_copy,
                                                          int32_t* __restrict__ offsets, int32_t* __restrict__ perm,
-                                                         int32_t* __restrict__ inv_perm,
-                                                         int32_t* __restrict__ row_token, int k,
+                                                         int32_t* __restrict__ inv_perm, int k, bool check_dups,
                                                          int32_t* __restrict__ flags) {
     constexpr int PER_WAVE = PERM_CHUNK / 4;
     __shared__ int32_t s_cnt[4][MAX_E];
@@ -204,33 +211,48 @@ __global__ __launch_bounds__(256) void permute_one_chunk(const int32_t* __restri
             inv_perm[i] = -1;
             continue;
         }
+        if (check_dups) {
+            const int first = i - i % k;
+            bool dup = false;
+            for (int q = first; q < i; ++q) dup |= ids[q] == e;
+            if (dup) flags[1] = 1;
+        }
         const int pos = (e ? s_off[e - 1] : 0) + s_cnt[wave][e] + my_rank[st];
         inv_perm[i] = pos;
         perm[pos] = i;
-        row_token[pos] = i / k;
     }
+}
+
+__global__ void fill_i32(int32_t* __restrict__ p, int n, int32_t v) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = v;
 }
 
 }  // namespace
 
-hipError_t launch_permute(moe_ctx* c, const int32_t* ids_in, int32_t* ids_copy, const float* w_in,
+// a fill kernel, not hipMemsetAsync: it stays correct when a caller records the call into a HIP graph
+hipError_t launch_fill_i32(hipStream_t stream, int32_t* p, int n, int32_t v) {
+    if (n > 0) hipLaunchKernelGGL(fill_i32, dim3((n + 255) / 256), dim3(256), 0, stream, p, n, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_permute(const permute_args& a, const int32_t* ids_in, int32_t* ids_copy, const float* w_in,
                           float* w_copy, int32_t* offsets, int32_t* perm, int32_t* inv_perm) {
-    const moe_dims& D = c->dims;
-    const int N = D.T * D.k;
+    const int N = a.T * a.k;
     const int n_chunks = (N + PERM_CHUNK - 1) / PERM_CHUNK;
     if (n_chunks == 1) {
-        hipLaunchKernelGGL(permute_one_chunk, dim3(1), dim3(256), 0, c->stream, ids_in, N, D.E, ids_copy, w_in, w_copy,
-                           offsets, perm, inv_perm, c->row_token, D.k, c->flags);
+        hipLaunchKernelGGL(permute_one_chunk, dim3(1), dim3(256), 0, a.stream, ids_in, N, a.E, ids_copy, w_in, w_copy,
+                           offsets, perm, inv_perm, a.k, a.check_dups, a.flags);
         return hipGetLastError();
     }
     if (n_chunks > 0)
-        hipLaunchKernelGGL(chunk_hist_rank, dim3(n_chunks), dim3(256), 0, c->stream, ids_in, N, D.E,
-                           c->chunk_counts, inv_perm, ids_copy);
-    hipLaunchKernelGGL(scan_chunks, dim3(1), dim3(256), 0, c->stream, c->chunk_counts, n_chunks, D.E, N,
+        hipLaunchKernelGGL(chunk_hist_rank, dim3(n_chunks), dim3(256), 0, a.stream, ids_in, N, a.E,
+                           a.chunk_counts, inv_perm, ids_copy);
+    hipLaunchKernelGGL(scan_chunks, dim3(1), dim3(256), 0, a.stream, a.chunk_counts, n_chunks, a.E, N,
                        offsets);
     if (N > 0)
-        hipLaunchKernelGGL(scatter, dim3((N + 255) / 256), dim3(256), 0, c->stream, ids_in, N, D.E,
-                           c->chunk_counts, offsets, w_in, w_copy, perm, inv_perm, c->row_token, D.k, c->flags);
+        hipLaunchKernelGGL(scatter, dim3((N + 255) / 256), dim3(256), 0, a.stream, ids_in, N, a.E,
+                           a.chunk_counts, offsets, w_in, w_copy, perm, inv_perm, a.k, a.check_dups, a.flags);
     return hipGetLastError();
 }
 

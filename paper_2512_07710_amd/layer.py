@@ -6,7 +6,6 @@ arithmetic happens inside libmoe355.
 """
 from __future__ import annotations
 
-import ctypes
 from typing import Dict, Optional
 
 import torch
@@ -35,8 +34,6 @@ class MoELayer:
         self.xs_tok = torch.empty((d // 128, max(T, 1)), dtype=torch.float32, device=dev)
         self.y_perm = torch.empty((N, d), dtype=torch.float32, device=dev)
         self.y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
-        self.yq = None          # 16-bit expert outputs [N,d] and their scales [N,d/128], allocated on first use
-        self.ys = None
 
     def close(self):
         if getattr(self, "ctx", None):
@@ -69,7 +66,7 @@ class MoELayer:
         B.moe_quantize_fp8(self.ctx, x, self.T, self.d, 128, None, 1, self.xq_tok, self.xs_tok)
 
     def expert_ffn_gather(self, w: Dict[str, torch.Tensor]):
-        B.moe_expert_ffn_fp8_gather(self.ctx, self.xq_tok, self.xs_tok, self.offsets, w["W1q"], w["W3q"], w["W2q"],
+        B.moe_expert_ffn_fp8_gather(self.ctx, self.xq_tok, self.xs_tok, self.perm, self.offsets, w["W1q"], w["W3q"], w["W2q"],
                                     w["s1"], w["s3"], w["s2"], self.y_perm)
 
     def expert_ffn(self, w: Dict[str, torch.Tensor]):
@@ -79,27 +76,10 @@ class MoELayer:
     def combine(self):
         B.moe_combine(self.ctx, self.y_perm, self.inv_perm, self.topk_w, self.y)
 
-    def expert_ffn_gather_i16(self, w: Dict[str, torch.Tensor]):
-        if self.yq is None:
-            N = max(self.N, 1)
-            self.yq = torch.empty((N, self.d), dtype=torch.int16, device=self.device)
-            self.ys = torch.empty((N, self.d // 128), dtype=torch.float32, device=self.device)
-        B.moe_expert_ffn_fp8_gather_i16(self.ctx, self.xq_tok, self.xs_tok, self.offsets, w["W1q"], w["W3q"],
-                                        w["W2q"], w["s1"], w["s3"], w["s2"], self.yq, self.ys)
-
-    def combine_i16(self):
-        B.moe_combine_i16(self.ctx, self.yq, self.ys, self.inv_perm, self.topk_w, self.y)
-
     # ---- whole layer ----------------------------------------------------------------
     # `fused` = True: activations quantised once per token, gathered inside the gate/up GEMM;
-    # False: the expert-ordered copy xq/xs is materialised first (same results bit for bit);
-    # "i16": as True, with the expert outputs stored as 16-bit block-scaled rows between the down GEMM and the combine
+    # False: the expert-ordered copy xq/xs is materialised first (same results bit for bit)
     def _ffn(self, x, w, fused):
-        if fused == "i16":
-            self.quantize_tokens(x)
-            self.expert_ffn_gather_i16(w)
-            self.combine_i16()
-            return self.y
         if fused:
             self.quantize_tokens(x)
             self.expert_ffn_gather(w)
@@ -119,13 +99,9 @@ class MoELayer:
 
     def hidden(self):
         """Copies of (hq [N,F] u8, hs [F/128,N] f32, group-major) written by the last expert_ffn call."""
-        a, b = B.moe_debug_hidden(self.ctx)
         N, F = max(self.N, 1), self.F
         hq = torch.empty((N, F), dtype=torch.uint8, device=self.device)
         hs = torch.empty((F // 128, N), dtype=torch.float32, device=self.device)
-        rt = ctypes.CDLL("libamdhip64.so")
-        rt.hipMemcpy.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int]
+        B.moe_debug_copy_hidden(self.ctx, hq, hs)
         torch.cuda.synchronize(self.device)
-        assert rt.hipMemcpy(hq.data_ptr(), a, hq.numel(), 3) == 0
-        assert rt.hipMemcpy(hs.data_ptr(), b, hs.numel() * 4, 3) == 0
         return hq, hs

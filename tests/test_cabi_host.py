@@ -44,6 +44,9 @@ def test_strerror_and_version(lib):
     (64, 128, 300, 2, 256),   # more experts than supported
     (-1, 128, 8, 2, 256),     # negative token count
     (64, 128, 32, 17, 256),   # k beyond the supported maximum
+    (1 << 20, 2048, 8, 2, 256),        # T*d = 2^31: the router's 32-bit byte offsets into x would wrap
+    (16, 1 << 16, 8, 2, 1 << 16),      # F*d = 2^32: byte offsets inside one expert's weight matrix would wrap
+    ((1 << 27) + 1, 128, 16, 8, 128),  # T*k beyond 2^30
 ])
 def test_create_rejects_bad_dims_without_a_device(lib, dims):
     d = binding._Dims(*dims)
@@ -61,11 +64,10 @@ def test_null_arguments_are_rejected(lib):
     assert lib.moe_route_replay_ids(None, None, None, None, None, None, None, None, None) == -1
     assert lib.moe_quantize_weights_fp8(None, None, 128, 128, None, None) == -1
     assert lib.moe_linear_fp8(None, None, None, 4, 128, None, None, 128, None) == -1
-    assert lib.moe_expert_ffn_fp8_gather(None, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.moe_expert_ffn_fp8_gather(*([None] * 12)) == -1
     assert lib.moe_expert_ffn_fp8(*([None] * 11)) == -1
     assert lib.moe_combine(*([None] * 5)) == -1
-    assert lib.moe_combine_i16(*([None] * 6)) == -1
-    assert lib.moe_expert_ffn_fp8_gather_i16(*([None] * 12)) == -1
+    assert lib.moe_debug_copy_hidden(None, None, None) == -1
     assert lib.moe_check_ids(None) == -1
 
 

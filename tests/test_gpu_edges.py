@@ -75,7 +75,7 @@ def test_empty_batch(gpu_lib):
         s2 = torch.ones((E, d // 128, F // 128), dtype=torch.float32, device=dev)
         y_perm = torch.empty((0, d), dtype=torch.float32, device=dev)
         gpu_lib.moe_expert_ffn_fp8(ctx, xq, xs, offsets, W, W, W2, s13, s13, s2, y_perm)
-        gpu_lib.moe_expert_ffn_fp8_gather(ctx, xq, xs, offsets, W, W, W2, s13, s13, s2, y_perm)
+        gpu_lib.moe_expert_ffn_fp8_gather(ctx, xq, xs, perm, offsets, W, W, W2, s13, s13, s2, y_perm)
         y = torch.empty((0, d), dtype=torch.bfloat16, device=dev)
         gpu_lib.moe_combine(ctx, y_perm, inv, w, y)
         torch.cuda.synchronize()

@@ -1,7 +1,14 @@
-"""GPU parity at the full workload sizes (configs 2, 3, 4), in the launch configuration the
-benchmark times.  Routing and permutation are checked in full; quantisation, the expert FFN
-and the combine are checked on sampled tokens / experts that the oracle evaluates one by one.
-Inputs are generated on the device and copied to the host for the oracle.
+"""GPU parity at the full workload sizes (configs 2, 3, 4), in the launch configuration the benchmark times.
+
+Configs 2 and 3: the oracle evaluates the WHOLE layer (every expert, every row, every token) and the
+whole-tensor relative L2 error is gated at 2e-3 with no allowance, for the expert outputs and for the layer
+output.  Config 4 (23 TFLOP of fp64 for the oracle): routing and permutation in full, the FFN stages on
+sampled experts, and the layer end to end on tokens 0..4095 (every one of which carries 20-sigma outliers),
+gated at 2e-3 outright, in routed and in replay mode.
+
+The oracle's work is split over several tests (32 experts each) that share one GPU run through a module-level
+cache, so that no single test is silent for long; the tests that state the gate evaluate whatever part a
+deselected sibling has left undone.  Inputs are generated on the device and copied to the host for the oracle.
 """
 import numpy as np
 import pytest
@@ -15,6 +22,10 @@ pytestmark = pytest.mark.gpu
 
 REL_L2_BAR = 2e-3
 GAP_BAR = 1e-4
+DEV = "cuda:0"
+EXPERT_CHUNK = 32
+CFG4_TOKENS = 4096
+WNAMES = ("W1q", "W3q", "W2q", "s1", "s3", "s2")
 
 
 def _bits(x):
@@ -26,6 +37,62 @@ def _rel_l2(a, b):
     return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-300))
 
 
+def _dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+# --------------------------------------------------------------------------- one GPU run per config, shared
+class _Run:
+    """Inputs, the GPU's outputs (materialised path) and the oracle's partial results of one config."""
+
+    def __init__(self, gpu_lib, ci):
+        self.lib = gpu_lib
+        self.cfg = cfg = CONFIGS[ci]
+        self.inp = inp = make_inputs(cfg, device=DEV)
+        self.layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
+        self.x_bits = _bits(inp["x"])
+        self.W_r = inp["W_r"].cpu().numpy()
+        self.bias = inp["sel_bias"].cpu().numpy() if inp.get("sel_bias") is not None else None
+        self.mode = "routed" if "routed" in cfg.modes else "replay"
+        if self.mode == "routed":
+            self.layer.forward_routed(inp["x"], inp["W_r"], inp.get("sel_bias"), inp, fused=False)
+        else:
+            self.log = (inp["logged_idx"], inp["logged_w"])
+            self.layer.forward_replay(inp["x"], self.log[0], self.log[1], inp, fused=False)
+        torch.cuda.synchronize()
+        assert gpu_lib.moe_check_ids(self.layer.ctx) == 0
+        L = self.layer
+        self.idx, self.w = L.topk_idx.cpu().numpy(), L.topk_w.cpu().numpy()
+        self.offsets, self.perm, self.inv_perm = L.offsets.cpu().numpy(), L.perm.cpu().numpy(), L.inv_perm.cpu().numpy()
+        self.y = L.y.clone()
+        self.hq, self.hs = L.hidden()
+        self.done = set()              # experts the oracle has evaluated
+        self.num = self.den = 0.0      # running squared error / norm of y_perm
+        self.y_perm_o = None           # the oracle's expert outputs (whole-tensor configs)
+        self.ref_rows = None           # config 4: oracle rows of the sampled tokens, [token, slot, d]
+
+    def weights(self, e):
+        return {n: self.inp[n][e].cpu().numpy() for n in WNAMES}
+
+    def close(self):
+        self.layer.close()
+        self.inp = None
+
+
+_current = {}
+
+
+def _run(gpu_lib, ci):
+    if _current.get("ci") != ci:
+        if "run" in _current:
+            _current.pop("run").close()
+            torch.cuda.empty_cache()
+        _current["ci"] = ci
+        _current["run"] = _Run(gpu_lib, ci)
+    return _current["run"]
+
+
+# --------------------------------------------------------------------------- checks
 def _check_routing_full(cfg, x_bits, W_r, bias, idx_g, w_g):
     idx_o, w_o, logits = om.route(x_bits, W_r, cfg.k, bias)
     score = logits if bias is None else logits + bias.astype(np.float64)[None, :]
@@ -44,161 +111,270 @@ def _check_routing_full(cfg, x_bits, W_r, bias, idx_g, w_g):
     assert np.all(np.abs(w_g[ok] - w_o[ok]) <= 1e-6 + 1e-5 * w_o[ok])
     for row in idx_g[:: max(1, cfg.T // 512)]:
         assert len(set(row.tolist())) == cfg.k
+    return idx_o, w_o
 
 
-def _fullsize(gpu_lib, cfg, mode, n_tokens_e2e):
-    dev = "cuda:0"
-    inp = make_inputs(cfg, device=dev)
-    layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
-    try:
-        x_bits = _bits(inp["x"])
-        bias = inp["sel_bias"].cpu().numpy() if inp.get("sel_bias") is not None else None
-        if mode == "routed":
-            layer.forward_routed(inp["x"], inp["W_r"], inp.get("sel_bias"), inp, fused=False)
-            torch.cuda.synchronize()
-            _check_routing_full(cfg, x_bits, inp["W_r"].cpu().numpy(), bias, layer.topk_idx.cpu().numpy(),
-                                layer.topk_w.cpu().numpy())
-        else:
-            if cfg.log == "zipf":
-                log_idx, log_w = inp["logged_idx"], inp["logged_w"]
-            else:   # the oracle's own routing decision serves as the log
-                oi, ow, _ = om.route(x_bits, inp["W_r"].cpu().numpy(), cfg.k, bias)
-                log_idx, log_w = torch.from_numpy(oi).to(dev), torch.from_numpy(ow).to(dev)
-            layer.forward_replay(inp["x"], log_idx, log_w, inp, fused=False)
-            torch.cuda.synchronize()
-            assert torch.equal(layer.topk_idx, log_idx) and torch.equal(layer.topk_w, log_w)
-        assert gpu_lib.moe_check_ids(layer.ctx) == 0
-        idx = layer.topk_idx.cpu().numpy()
-        w = layer.topk_w.cpu().numpy()
+def _check_permutation_full(r):
+    offsets, perm, inv_perm = om.permute(r.idx, r.cfg.E)
+    assert np.array_equal(r.offsets, offsets)
+    assert np.array_equal(r.perm, perm)
+    assert np.array_equal(r.inv_perm, inv_perm)
+    counts = np.diff(offsets)
+    print(f"[{r.cfg.name}/{r.mode}] rows per expert: min {counts.min()} median {int(np.median(counts))} "
+          f"max {counts.max()}, {int((counts == 0).sum())} empty")
 
-        # permutation: bit-exact, in full
-        offsets, perm, inv_perm = om.permute(idx, cfg.E)
-        assert np.array_equal(layer.offsets.cpu().numpy(), offsets)
-        assert np.array_equal(layer.perm.cpu().numpy(), perm)
-        assert np.array_equal(layer.inv_perm.cpu().numpy(), inv_perm)
-        counts = np.diff(offsets)
-        print(f"[{cfg.name}/{mode}] rows per expert: min {counts.min()} median {int(np.median(counts))} max {counts.max()}, "
-              f"{int((counts == 0).sum())} empty")
 
-        # sampled experts: the busiest, the emptiest non-empty one, and one in between
-        order = np.argsort(counts)
-        nonempty = order[counts[order] > 0]
-        experts = sorted({int(nonempty[0]), int(nonempty[len(nonempty) // 2]), int(nonempty[-1])})
-        if cfg.log == "zipf":
-            experts = sorted(set(experts) | {0})
-        hq_all, hs_all = layer.hidden()
-        tot_num = tot_den = 0.0
-        for e in experts:
-            a, b = int(offsets[e]), int(offsets[e + 1])
-            if b - a > 1280:                         # bound the oracle's work: first and last 640 rows
-                rows = np.r_[a:a + 640, b - 640:b]
-            else:
-                rows = np.arange(a, b)
-            xq_o, xs_o = om.quantize_rows(ff.bf16_bits_to_f64(x_bits[perm[rows] // cfg.k]))
-            rt = torch.from_numpy(rows).to(dev)
-            assert np.array_equal(layer.xq[rt].cpu().numpy(), xq_o), f"xq rows of expert {e}"
-            assert np.array_equal(layer.xs[:, rt].cpu().numpy().T, xs_o), f"xs rows of expert {e}"
-            We = {n: inp[n][e].cpu().numpy() for n in ("W1q", "W3q", "W2q", "s1", "s3", "s2")}
-            y_o, hq_o, hs_o = om.expert_ffn_rows(xq_o, xs_o, We["W1q"], We["s1"], We["W3q"], We["s3"], We["W2q"], We["s2"])
-            hq_g, hs_g = hq_all[rt].cpu().numpy(), np.ascontiguousarray(hs_all[:, rt].cpu().numpy().T)
-            mism = float((hq_g != hq_o).mean())
-            y_g = layer.y_perm[rt].cpu().numpy()
-            rel = _rel_l2(y_g, y_o)
-            iso = _rel_l2(y_g, om.block_scaled_matmul(hq_g, hs_g, We["W2q"], We["s2"]))
-            print(f"[{cfg.name}/{mode}] expert {e}: {rows.size} of {b - a} rows, hq mismatch {mism:.2e}, "
-                  f"y_perm rel-L2 {rel:.3e}, GEMM2 alone {iso:.3e}")
-            assert mism < 5e-3 and np.allclose(hs_g, hs_o, rtol=2e-4)
-            assert rel <= REL_L2_BAR and iso <= 1e-4
-            tot_num += float(np.linalg.norm(y_g.astype(np.float64) - y_o) ** 2)
-            tot_den += float(np.linalg.norm(y_o) ** 2)
-        print(f"[{cfg.name}/{mode}] y_perm rel-L2 over all sampled rows {np.sqrt(tot_num / tot_den):.3e}")
+def _check_expert_rows(r, e, rows, keep):
+    """Stage-by-stage comparison of sorted rows `rows` (all of expert e) with the oracle; adds their squared
+    error to the run's totals and, if keep, stores the oracle's y_perm rows."""
+    cfg, L = r.cfg, r.layer
+    xq_o, xs_o = om.quantize_rows(ff.bf16_bits_to_f64(r.x_bits[r.perm[rows] // cfg.k]))
+    rt = _dev(rows)
+    assert np.array_equal(L.xq[rt].cpu().numpy(), xq_o), f"xq rows of expert {e}"
+    assert np.array_equal(L.xs[:, rt].cpu().numpy().T, xs_o), f"xs rows of expert {e}"
+    We = r.weights(e)
+    y_o, hq_o, hs_o = om.expert_ffn_rows(xq_o, xs_o, We["W1q"], We["s1"], We["W3q"], We["s3"], We["W2q"], We["s2"])
+    hq_g, hs_g = r.hq[rt].cpu().numpy(), np.ascontiguousarray(r.hs[:, rt].cpu().numpy().T)
+    mism = float((hq_g != hq_o).mean())
+    y_g = L.y_perm[rt].cpu().numpy()
+    rel = _rel_l2(y_g, y_o)
+    iso = _rel_l2(y_g, om.block_scaled_matmul(hq_g, hs_g, We["W2q"], We["s2"]))
+    assert mism < 5e-3 and np.allclose(hs_g, hs_o, rtol=2e-4), f"expert {e}: hq mismatch {mism:.2e}"
+    assert iso <= 1e-4, f"expert {e}: down projection alone {iso:.3e}"
+    # a single expert's few hundred rows scatter around the whole-tensor figure, which is the one that is gated
+    assert rel <= 1.5 * REL_L2_BAR, f"expert {e}: y_perm rel-L2 {rel:.3e}"
+    r.num += float(np.linalg.norm(y_g.astype(np.float64) - y_o) ** 2)
+    r.den += float(np.linalg.norm(y_o) ** 2)
+    if keep:
+        r.y_perm_o[rows] = y_o
+    return rows.size, mism, rel, iso
 
-        # combine alone on sampled tokens: the oracle's combine of the GPU's own y_perm rows
-        rng = np.random.default_rng(cfg.seed)
-        toks = np.sort(rng.choice(cfg.T, size=min(256, cfg.T), replace=False))
-        y_g = layer.y[torch.from_numpy(toks).to(dev)].float().cpu().numpy()
-        rows = inv_perm.reshape(cfg.T, cfg.k)[toks]
-        yp = layer.y_perm[torch.from_numpy(rows.reshape(-1)).to(dev)].cpu().numpy().astype(np.float64)
-        yp = yp.reshape(toks.size, cfg.k, cfg.d)
-        y_ref = np.einsum("tk,tkd->td", w[toks].astype(np.float64), yp)
-        ref_bits = ff.bf16_bits_to_f64(ff.f64_to_bf16_bits(y_ref))
-        flips = float((y_g != ref_bits).mean())
-        assert flips < 1e-3 and _rel_l2(y_g, ref_bits) <= 1e-6 + 0.01 * np.sqrt(flips)
 
-        # end to end on sampled tokens, grouped by expert so that each expert is dequantised once
-        e2e = toks[:n_tokens_e2e]
-        y_ref64 = np.zeros((e2e.size, cfg.d))
-        xq_s, xs_s = om.quantize_rows(ff.bf16_bits_to_f64(x_bits[e2e]))
-        pairs = {}
-        for a, t in enumerate(e2e):
-            for j in range(cfg.k):
-                pairs.setdefault(int(idx[t, j]), []).append((a, j))
-        for e, lst in sorted(pairs.items()):
-            sel = np.array([a for a, _ in lst])
-            We = {n: inp[n][e].cpu().numpy() for n in ("W1q", "W3q", "W2q", "s1", "s3", "s2")}
-            y_e, _, _ = om.expert_ffn_rows(xq_s[sel], xs_s[sel], We["W1q"], We["s1"], We["W3q"], We["s3"], We["W2q"], We["s2"])
-            for (a, j), row in zip(lst, y_e):
-                y_ref64[a] += float(w[e2e[a], j]) * row
-        # the oracle sums the slots in order j; regrouping by expert changes only fp64 rounding
-        ref = ff.bf16_bits_to_f64(ff.f64_to_bf16_bits(y_ref64))
-        got = layer.y[torch.from_numpy(e2e).to(dev)].float().cpu().numpy()
-        num_t = np.sum((got - ref) ** 2, axis=1)
-        den = float(np.sum(ref ** 2))
-        est = float(np.sqrt(num_t.sum() / den))
-        # standard error of the sampled ratio (tokens are the sampling unit)
-        se = float(0.5 * np.sqrt(e2e.size * np.var(num_t)) / den / max(est, 1e-30))
-        print(f"[{cfg.name}/{mode}] layer rel-L2 over {e2e.size} end-to-end tokens {est:.3e} +- {se:.1e} "
-              f"(bar {REL_L2_BAR}, whole tensor), per-token max {np.sqrt(num_t / np.sum(ref ** 2, axis=1)).max():.3e}")
-        # the bar is a whole-tensor figure; a token sample may not exceed it by more than its sampling error
-        assert est - 2.0 * se <= REL_L2_BAR
-        # the gather-fused path (activations quantised once per token, gathered inside the gate/up GEMM) must
-        # reproduce the materialised path bit for bit at full size
-        y_mat = layer.y.clone()
-        hq_mat, hs_mat = layer.hidden()
-        layer.y.zero_()
-        layer._ffn(inp["x"], inp, fused=True)
+def _whole_experts(r, experts):
+    cfg = r.cfg
+    if r.y_perm_o is None:
+        r.y_perm_o = np.zeros((cfg.N, cfg.d), dtype=np.float64)
+    worst = (0.0, -1)
+    for e in experts:
+        if e in r.done:
+            continue
+        a, b = int(r.offsets[e]), int(r.offsets[e + 1])
+        if b > a:
+            _, mism, rel, iso = _check_expert_rows(r, e, np.arange(a, b), keep=True)
+            worst = max(worst, (rel, e))
+        r.done.add(e)
+    if worst[1] >= 0:
+        print(f"[{cfg.name}/{r.mode}] experts {min(experts)}..{max(experts)}: largest per-expert y_perm rel-L2 "
+              f"{worst[0]:.3e} (expert {worst[1]}); running whole-tensor figure {np.sqrt(r.num / r.den):.3e}")
+
+
+def _chunks(E):
+    return [list(range(a, min(a + EXPERT_CHUNK, E))) for a in range(0, E, EXPERT_CHUNK)]
+
+
+def _combine_alone(r, y_gpu):
+    """The oracle's combine of the GPU's own y_perm, whole tensor: only bf16 roundings may fall the other way."""
+    cfg = r.cfg
+    yp = r.layer.y_perm.cpu().numpy().astype(np.float64)
+    _, bits = om.combine(yp, r.inv_perm, r.w)
+    ref = ff.bf16_bits_to_f64(bits)
+    y_g = y_gpu.float().cpu().numpy()
+    flips = float((y_g != ref).mean())
+    assert flips < 1e-3 and _rel_l2(y_g, ref) <= 1e-6 + 0.01 * np.sqrt(flips)
+    return flips
+
+
+def _combine_alone_sampled(r, toks):
+    """The same on sampled tokens (config 4: the whole y_perm is 7.5 GB)."""
+    cfg = r.cfg
+    rows = r.inv_perm.reshape(cfg.T, cfg.k)[toks]
+    yp = r.layer.y_perm[_dev(rows.reshape(-1))].cpu().numpy().astype(np.float64).reshape(toks.size, cfg.k, cfg.d)
+    y_ref = np.zeros((toks.size, cfg.d))
+    for j in range(cfg.k):
+        y_ref += r.w[toks, j].astype(np.float64)[:, None] * yp[:, j]
+    ref = ff.bf16_bits_to_f64(ff.f64_to_bf16_bits(y_ref))
+    y_g = r.y[_dev(toks)].float().cpu().numpy()
+    flips = float((y_g != ref).mean())
+    assert flips < 1e-3 and _rel_l2(y_g, ref) <= 1e-6 + 0.01 * np.sqrt(flips)
+
+
+def _fused_is_bit_identical(r):
+    """The gather-fused path (activations quantised once per token, gathered inside the gate/up GEMM) must
+    reproduce the materialised path bit for bit at full size."""
+    L = r.layer
+    L.y.zero_()
+    L._ffn(r.inp["x"], r.inp, fused=True)
+    torch.cuda.synchronize()
+    hq_f, hs_f = L.hidden()
+    assert torch.equal(r.hq, hq_f) and torch.equal(r.hs.view(torch.int32), hs_f.view(torch.int32))
+    assert torch.equal(r.y.view(torch.int16), L.y.view(torch.int16))
+
+
+def _whole_tensor_gate(gpu_lib, ci):
+    r = _run(gpu_lib, ci)
+    cfg = r.cfg
+    _whole_experts(r, range(cfg.E))                       # whatever the chunk tests have not done yet
+    rel_perm = float(np.sqrt(r.num / r.den))
+    y_o, bits = om.combine(r.y_perm_o, r.inv_perm, r.w)
+    ref = ff.bf16_bits_to_f64(bits)
+    y_g = r.y.float().cpu().numpy()
+    rel = _rel_l2(y_g, ref)
+    per_tok = np.sqrt(np.sum((y_g - ref) ** 2, axis=1) / np.maximum(np.sum(ref ** 2, axis=1), 1e-300))
+    flips = _combine_alone(r, r.y)
+    print(f"[{cfg.name}/{r.mode}] WHOLE TENSOR: layer rel-L2 {rel:.3e}, y_perm rel-L2 {rel_perm:.3e} (bar {REL_L2_BAR}); "
+          f"per-token max {per_tok.max():.3e}; combine alone: {flips:.2e} bf16 roundings differ")
+    assert rel_perm <= REL_L2_BAR
+    assert rel <= REL_L2_BAR
+    _fused_is_bit_identical(r)
+
+
+# --------------------------------------------------------------------------- config 2: routed, balanced by a bias
+def test_config2_routing_and_permutation(gpu_lib):
+    r = _run(gpu_lib, 2)
+    _check_routing_full(r.cfg, r.x_bits, r.W_r, r.bias, r.idx, r.w)
+    _check_permutation_full(r)
+
+
+@pytest.mark.parametrize("chunk", _chunks(CONFIGS[2].E), ids=lambda c: f"experts{c[0]}-{c[-1]}")
+def test_config2_every_expert(gpu_lib, chunk):
+    _whole_experts(_run(gpu_lib, 2), chunk)
+
+
+def test_config2_whole_tensor_bar(gpu_lib):
+    _whole_tensor_gate(gpu_lib, 2)
+
+
+# --------------------------------------------------------------------------- config 3: Zipf replay log
+def test_config3_log_and_permutation(gpu_lib):
+    r = _run(gpu_lib, 3)
+    assert torch.equal(r.layer.topk_idx, r.log[0]) and torch.equal(r.layer.topk_w, r.log[1])
+    _check_permutation_full(r)
+    # what the generator promises: about 3 % of the tokens carry ids the router would not have chosen
+    idx_o, _, _ = om.route(r.x_bits, r.W_r, r.cfg.k, None)
+    foreign = np.any(np.sort(idx_o, 1) != np.sort(r.idx, 1), axis=1).mean()
+    print(f"[{r.cfg.name}] {100 * foreign:.2f} % of the tokens carry ids that differ from the router's own")
+    assert 0.02 <= foreign <= 0.04
+
+
+@pytest.mark.parametrize("chunk", _chunks(CONFIGS[3].E), ids=lambda c: f"experts{c[0]}-{c[-1]}")
+def test_config3_every_expert(gpu_lib, chunk):
+    _whole_experts(_run(gpu_lib, 3), chunk)
+
+
+def test_config3_whole_tensor_bar(gpu_lib):
+    _whole_tensor_gate(gpu_lib, 3)
+
+
+# --------------------------------------------------------------------------- config 4
+def test_config4_routing_and_permutation(gpu_lib):
+    r = _run(gpu_lib, 4)
+    r.oracle_route = _check_routing_full(r.cfg, r.x_bits, r.W_r, r.bias, r.idx, r.w)
+    _check_permutation_full(r)
+
+
+def test_config4_stages_on_sampled_experts(gpu_lib):
+    """Quantised activations bit-exact, hidden codes, scales and expert outputs of the busiest expert, the
+    emptiest and one in between (first and last 640 rows of each)."""
+    r = _run(gpu_lib, 4)
+    counts = np.diff(r.offsets)
+    order = np.argsort(counts)
+    nonempty = order[counts[order] > 0]
+    for e in sorted({int(nonempty[0]), int(nonempty[len(nonempty) // 2]), int(nonempty[-1])}):
+        a, b = int(r.offsets[e]), int(r.offsets[e + 1])
+        rows = np.r_[a:a + 640, b - 640:b] if b - a > 1280 else np.arange(a, b)
+        n, mism, rel, iso = _check_expert_rows(r, e, rows, keep=False)
+        print(f"[{r.cfg.name}] expert {e}: {n} of {b - a} rows, hq mismatch {mism:.2e}, y_perm rel-L2 {rel:.3e}, "
+              f"GEMM2 alone {iso:.3e}")
+
+
+def _cfg4_reference_rows(r, experts):
+    """Oracle expert outputs for the (token, slot) pairs of tokens 0..CFG4_TOKENS-1 that go to `experts`,
+    following the GPU's own routing decision; each expert is dequantised once."""
+    cfg = r.cfg
+    if r.ref_rows is None:
+        r.ref_rows = np.zeros((CFG4_TOKENS, cfg.k, cfg.d), dtype=np.float64)
+        r.xq_s, r.xs_s = om.quantize_rows(ff.bf16_bits_to_f64(r.x_bits[:CFG4_TOKENS]))
+        r.done4 = set()
+    idx = r.idx[:CFG4_TOKENS]
+    for e in experts:
+        if e in r.done4:
+            continue
+        tok, slot = np.nonzero(idx == e)
+        if tok.size:
+            We = r.weights(e)
+            y_e, _, _ = om.expert_ffn_rows(r.xq_s[tok], r.xs_s[tok], We["W1q"], We["s1"], We["W3q"], We["s3"],
+                                           We["W2q"], We["s2"])
+            r.ref_rows[tok, slot] = y_e
+        r.done4.add(e)
+
+
+@pytest.mark.parametrize("chunk", _chunks(CONFIGS[4].E), ids=lambda c: f"experts{c[0]}-{c[-1]}")
+def test_config4_reference_rows(gpu_lib, chunk):
+    _cfg4_reference_rows(_run(gpu_lib, 4), chunk)
+
+
+def _sample_gate(r, y_gpu, w, label):
+    """Layer output of tokens 0..CFG4_TOKENS-1 against the oracle: y = sum over slots, in slot order, of
+    w * expert row, rounded to bf16 once."""
+    cfg = r.cfg
+    y_ref = np.zeros((CFG4_TOKENS, cfg.d), dtype=np.float64)
+    for j in range(cfg.k):
+        y_ref += w[:CFG4_TOKENS, j].astype(np.float64)[:, None] * r.ref_rows[:, j]
+    ref = ff.bf16_bits_to_f64(ff.f64_to_bf16_bits(y_ref))
+    got = y_gpu[:CFG4_TOKENS].float().cpu().numpy()
+    num_t = np.sum((got - ref) ** 2, axis=1)
+    den = float(np.sum(ref ** 2))
+    est = float(np.sqrt(num_t.sum() / den))
+    se = float(0.5 * np.sqrt(CFG4_TOKENS * np.var(num_t)) / den / max(est, 1e-30))   # tokens are the sampling unit
+    halves = [float(np.sqrt(num_t[h::2].sum() / np.sum(ref[h::2] ** 2))) for h in (0, 1)]
+    print(f"[{cfg.name}/{label}] layer rel-L2 over tokens 0..{CFG4_TOKENS - 1}: {est:.3e} +- {se:.1e} (bar {REL_L2_BAR}); "
+          f"even / odd tokens {halves[0]:.3e} / {halves[1]:.3e}; per-token max "
+          f"{np.sqrt(num_t / np.sum(ref ** 2, axis=1)).max():.3e}")
+    assert est <= REL_L2_BAR
+
+
+def test_config4_routed_sample_bar(gpu_lib):
+    r = _run(gpu_lib, 4)
+    _cfg4_reference_rows(r, range(r.cfg.E))
+    _sample_gate(r, r.y, r.w, "routed")
+    _combine_alone_sampled(r, np.sort(np.random.default_rng(r.cfg.seed).choice(r.cfg.T, size=512, replace=False)))
+    _fused_is_bit_identical(r)
+
+
+def test_config4_replay_sample_bar(gpu_lib):
+    """Replay of the ORACLE's routing decision (ids and fp64-computed weights as the log), and replay of the
+    GPU's own decision, which must reproduce the routed output bit for bit."""
+    r = _run(gpu_lib, 4)
+    cfg, L = r.cfg, r.layer
+    _cfg4_reference_rows(r, range(cfg.E))
+    if not hasattr(r, "oracle_route"):
+        r.oracle_route = om.route(r.x_bits, r.W_r, cfg.k, r.bias)[:2]
+    idx_o, w_o = r.oracle_route
+    # the reference rows follow the GPU's routed ids: they serve the replay of the oracle's log wherever the two
+    # decisions agree, which the routing test shows to be every token with a clear gap
+    same = np.all(idx_o[:CFG4_TOKENS] == r.idx[:CFG4_TOKENS], axis=1)
+    assert same.all(), f"{int((~same).sum())} sampled tokens were routed differently by the oracle"
+    log_idx, log_w = _dev(idx_o), _dev(w_o)
+    L.forward_replay(r.inp["x"], log_idx, log_w, r.inp, fused=False)
+    torch.cuda.synchronize()
+    assert torch.equal(L.topk_idx, log_idx) and torch.equal(L.topk_w, log_w)
+    offsets, perm, inv_perm = om.permute(idx_o, cfg.E)
+    assert np.array_equal(L.offsets.cpu().numpy(), offsets)
+    assert np.array_equal(L.perm.cpu().numpy(), perm)
+    assert np.array_equal(L.inv_perm.cpu().numpy(), inv_perm)
+    _sample_gate(r, L.y, w_o, "replay of the oracle's log")
+    # the GPU's own decision as the log: same bits as routed mode, on both FFN paths
+    own_idx, own_w = _dev(r.idx), _dev(r.w)
+    for fused in (False, True):
+        L.y.zero_()
+        L.forward_replay(r.inp["x"], own_idx, own_w, r.inp, fused=fused)
         torch.cuda.synchronize()
-        hq_f, hs_f = layer.hidden()
-        assert torch.equal(hq_mat, hq_f) and torch.equal(hs_mat.view(torch.int32), hs_f.view(torch.int32))
-        assert torch.equal(y_mat.view(torch.int16), layer.y.view(torch.int16))
-
-        # the 16-bit expert-output path at full size: sampled rows of codes and scales are exactly the oracle's
-        # row quantisation of the fp32 rows above, and the same end-to-end tokens keep the bar
-        rows_s = np.unique(rng.integers(0, cfg.N, size=512))
-        yp_rows = layer.y_perm[torch.from_numpy(rows_s).to(dev)].cpu().numpy().astype(np.float64)
-        layer.y.zero_()
-        layer._ffn(inp["x"], inp, fused="i16")
-        torch.cuda.synchronize()
-        yq_o, ys_o = om.quantize_rows_i16(yp_rows)
-        sel = torch.from_numpy(rows_s).to(dev)
-        assert np.array_equal(layer.yq[sel].cpu().numpy(), yq_o)
-        assert np.array_equal(layer.ys[sel].cpu().numpy(), ys_o)
-        got16 = layer.y[torch.from_numpy(e2e).to(dev)].float().cpu().numpy()
-        num16 = np.sum((got16 - ref) ** 2, axis=1)
-        est16 = float(np.sqrt(num16.sum() / den))
-        se16 = float(0.5 * np.sqrt(e2e.size * np.var(num16)) / den / max(est16, 1e-30))
-        drift = _rel_l2(layer.y.float().cpu().numpy(), y_mat.float().cpu().numpy())
-        print(f"[{cfg.name}/{mode}] 16-bit expert outputs: layer rel-L2 {est16:.3e} +- {se16:.1e}; whole tensor vs the "
-              f"fp32-row path {drift:.3e}")
-        assert est16 - 2.0 * se16 <= REL_L2_BAR
-        assert drift <= 1e-3
-        layer.yq = layer.ys = None
-        return y_mat
-    finally:
-        layer.close()
+        assert torch.equal(L.y.view(torch.int16), r.y.view(torch.int16))
 
 
-def test_config2_balanced_routed(gpu_lib):
-    _fullsize(gpu_lib, CONFIGS[2], "routed", n_tokens_e2e=256)
-
-
-def test_config3_zipf_replay(gpu_lib):
-    _fullsize(gpu_lib, CONFIGS[3], "replay", n_tokens_e2e=256)
-
-
-def test_config4_routed(gpu_lib):
-    _fullsize(gpu_lib, CONFIGS[4], "routed", n_tokens_e2e=128)
-
-
-def test_config4_replay(gpu_lib):
-    _fullsize(gpu_lib, CONFIGS[4], "replay", n_tokens_e2e=128)
+def test_release_cached_run():
+    """Frees the device memory the shared run holds (11 GB of expert weights at config 4)."""
+    if "run" in _current:
+        _current.pop("run").close()
+        _current.clear()
+        torch.cuda.empty_cache()

@@ -278,8 +278,13 @@ def test_replay_rejects_nothing_but_flags_bad_ids(gpu_lib):
         layer.close()
 
 
-def test_zeroed_expert_and_integer_exactness(gpu_lib):
-    """Unit scales + small-integer codes: fp32 accumulation is exact, so y_perm must match exactly."""
+def test_zeroed_expert_contributes_exactly_zero(gpu_lib):
+    """Unit weight scales and small-integer codes, one expert's down projection all zero.  That expert's rows
+    of y_perm must be exactly 0.  g and u are exact integers on both sides here, so many h/s land on e4m3
+    ties and the few ulps between the fp32 and the fp64 silu decide them: the hidden codes are compared by
+    mismatch rate (each mismatch one code step), and the down projection is compared on the GPU's own
+    codes.  (Exactness of the fp32 accumulation itself is pinned through moe_linear_fp8 in
+    test_linear_small_integer_codes_are_exact.)"""
     cfg = MoEConfig("ints", T=96, d=256, E=3, k=2, F=128, modes=("replay",), seed=9)
     rng = np.random.default_rng(9)
     pool = ff.e4m3_encode(np.array([0, 1, 2, -1, -2, 0.5, -0.5, 0], dtype=np.float64))
@@ -306,7 +311,18 @@ def test_zeroed_expert_and_integer_exactness(gpu_lib):
         y_g = layer.y_perm.cpu().numpy()
         a, b = offsets[1], offsets[2]
         assert b > a and np.all(y_g[a:b] == 0.0)
-        assert _rel_l2(y_g, y_o) <= REL_L2_BAR
+        hq_g, hs_g = layer.hidden()
+        hq_g, hs_g = hq_g.cpu().numpy(), np.ascontiguousarray(hs_g.cpu().numpy().T)
+        assert np.allclose(hs_g, hs_o, rtol=2e-4)
+        diff = hq_g != hq_o
+        # a mismatch is one code step (adjacent magnitudes, same sign); +0/-0 are codes 0x00/0x80
+        step = np.abs((hq_g & 0x7F).astype(np.int32) - (hq_o & 0x7F).astype(np.int32))
+        print(f"[ints] hidden code mismatches {diff.mean():.2e}, largest step {step.max()}")
+        assert diff.mean() < 2e-2 and step.max() <= 1
+        for e in range(3):
+            a, b = int(offsets[e]), int(offsets[e + 1])
+            iso = om.block_scaled_matmul(hq_g[a:b], hs_g[a:b], W2q[e], s2[e])
+            assert _rel_l2(y_g[a:b], iso) <= 1e-4
     finally:
         layer.close()
 

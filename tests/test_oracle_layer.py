@@ -424,50 +424,3 @@ def test_quantize_blocks_invariants_and_torch_recipe():
     qb, sb = om.quantize_blocks(wr)
     qr, sr = om.quantize_rows(wr)
     assert np.array_equal(qb, qr) and np.array_equal(np.repeat(sb, 128, axis=0), sr)
-
-
-# --------------------------------------------------------------------------- 16-bit storage of the expert outputs
-def test_quantize_rows_i16_invariants_and_special_cases():
-    rng = np.random.default_rng(17)
-    y = (rng.standard_normal((37, 384)) * np.exp(rng.standard_normal((37, 1)))).astype(np.float32).astype(np.float64)
-    y[3, 128:256] = 0.0                                    # an all-zero group
-    y[5, :128] = np.arange(128) - 64.0                     # small integers
-    y[6, :128] = 0.0
-    y[6, 17] = -2.5                                        # a single non-zero element owns the scale
-    q, s = om.quantize_rows_i16(y)
-    assert q.dtype == np.int16 and s.dtype == np.float32 and q.shape == (37, 384) and s.shape == (37, 3)
-    yg = y.reshape(37, 3, 128)
-    qg = q.reshape(37, 3, 128).astype(np.int64)
-    amax = np.abs(yg).max(axis=2)
-    nz = amax > 0
-    assert np.all(s[~nz] == 1.0) and not qg[~nz].any()
-    assert np.all(s[nz] == (amax[nz] / 32767.0).astype(np.float32))
-    assert np.all(np.abs(qg).max(axis=2)[nz] == 32767)     # the group maximum lands on the largest code
-    assert np.abs(qg).max() <= 32767
-    # rounding error at most half a step (plus the fp32 roundings of the multiplier, the scale and the product)
-    err = np.abs(yg - qg * s.astype(np.float64)[:, :, None])
-    assert np.all(err <= 0.5 * s.astype(np.float64)[:, :, None] * (1 + 1e-6) + np.abs(yg) * 2.0 ** -21)
-    # sign symmetry, and scaling a row by a power of two scales the scale and keeps the codes
-    q2, s2 = om.quantize_rows_i16(-y)
-    assert np.array_equal(q2, -q) and np.array_equal(s2, s)
-    q3, s3 = om.quantize_rows_i16(y * 8.0)
-    assert np.array_equal(q3, q) and np.array_equal(s3[nz], s[nz] * np.float32(8.0)) and np.all(s3[~nz] == 1.0)
-    # the single-element group: code -32767 exactly, scale 2.5/32767
-    assert q[6, 17] == -32767 and s[6, 0] == np.float32(2.5 / 32767.0)
-    # round half to even at an exact tie: amax = 32767 makes the scale 1, so codes are rint of the values
-    t = np.zeros((1, 128))
-    t[0, 0] = 32767.0
-    t[0, 1:5] = [0.5, 1.5, 2.5, -3.5]
-    qt, st = om.quantize_rows_i16(t)
-    assert st[0, 0] == 1.0 and qt[0, :5].tolist() == [32767, 0, 2, 2, -4]
-    # relative size of what the format loses: about 2^-16 of the group maximum
-    deq = om.dequantize_rows_i16(q, s)
-    assert np.linalg.norm(deq - y) / np.linalg.norm(y) < 1e-4
-    # same recipe written with torch's float32 ops
-    yt = torch.from_numpy(y.astype(np.float32)).view(37, 3, 128)
-    at = yt.abs().amax(dim=2)
-    stt = torch.where(at == 0, torch.ones_like(at), at / 32767.0)
-    # (tensor / tensor: a scalar numerator would make torch multiply by a reciprocal, one rounding more)
-    mtt = torch.where(at == 0, torch.ones_like(at), torch.full_like(at, 32767.0) / at)
-    qtt = torch.round(yt * mtt[:, :, None]).to(torch.int16).view(37, 384).numpy()
-    assert np.array_equal(stt.numpy(), s) and np.array_equal(qtt, q)
