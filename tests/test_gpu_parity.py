@@ -260,20 +260,51 @@ def test_quantize_plain_and_edge_values(gpu_lib):
 
 
 def test_replay_rejects_nothing_but_flags_bad_ids(gpu_lib):
+    """Ids outside [0,E) and ids repeated inside a token never fault: the call goes through, a device flag is
+    raised that moe_check_ids reports once, and the permutation is the stable sort of what was given."""
     cfg = MoEConfig("bad", T=16, d=128, E=4, k=2, F=128, modes=("replay",))
     layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F)
     try:
-        idx = torch.randint(0, 4, (16, 2), dtype=torch.int32)
+        rng = np.random.default_rng(16)
+        good = np.stack([rng.permutation(4)[:2] for _ in range(16)]).astype(np.int32)     # distinct inside a token
+        w = torch.full((16, 2), 0.5)
+        idx = torch.from_numpy(good.copy())
         idx[5, 1] = 9
         idx[6, 0] = -2
-        w = torch.full((16, 2), 0.5)
         layer.route_replay(None, idx.cuda(), w.cuda())
         assert gpu_lib.moe_check_ids(layer.ctx) == -3
-        idx[5, 1] = 1
-        idx[6, 0] = 2
-        layer.route_replay(None, idx.cuda(), w.cuda())
+        assert gpu_lib.moe_check_ids(layer.ctx) == 0                   # reported once, then cleared
+        layer.route_replay(None, torch.from_numpy(good).cuda(), w.cuda())
         assert gpu_lib.moe_check_ids(layer.ctx) == 0
-        _check_permutation(idx.numpy(), 4, layer)
+        _check_permutation(good, 4, layer)
+        # a token that names the same expert twice: flagged, and still sorted like any other assignment
+        dup = good.copy()
+        dup[11, 1] = dup[11, 0]
+        layer.route_replay(None, torch.from_numpy(dup).cuda(), w.cuda())
+        assert gpu_lib.moe_check_ids(layer.ctx) == -3
+        _check_permutation(dup, 4, layer)
+        assert gpu_lib.moe_check_ids(layer.ctx) == 0
+    finally:
+        layer.close()
+
+
+@pytest.mark.parametrize("T,E,k", [(5000, 64, 6), (300, 200, 16)])
+def test_replay_duplicate_check_at_several_chunks(gpu_lib, T, E, k):
+    """The duplicate check in the three-kernel permutation (more than 2048 assignments) and in the single-block
+    one: a clean log passes, one repeated id anywhere in it is found."""
+    rng = np.random.default_rng(T)
+    good = np.stack([rng.permutation(E)[:k] for _ in range(T)]).astype(np.int32)
+    w = torch.full((T, k), 1.0 / k)
+    layer = gpu_lib.MoELayer(T, 128, E, k, 128)
+    try:
+        layer.route_replay(None, torch.from_numpy(good).cuda(), w.cuda())
+        assert gpu_lib.moe_check_ids(layer.ctx) == 0
+        for t, a, b in ((0, 0, k - 1), (T - 1, k - 2, k - 1), (T // 2, 1, 3)):
+            dup = good.copy()
+            dup[t, b] = dup[t, a]
+            layer.route_replay(None, torch.from_numpy(dup).cuda(), w.cuda())
+            assert gpu_lib.moe_check_ids(layer.ctx) == -3, (t, a, b)
+            _check_permutation(dup, E, layer)
     finally:
         layer.close()
 
