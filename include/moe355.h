@@ -87,6 +87,22 @@ int moe_route_replay(moe_ctx* ctx, const uint16_t* x_bf16, const int32_t* logged
                      const float* logged_w, int32_t* topk_idx, float* topk_w,
                      int32_t* offsets, int32_t* perm, int32_t* inv_perm);
 
+/* moe_route_replay for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  It needs no context: the permutation's workspace (per-chunk
+ * histograms) lives in a static 512 KiB device array inside the library, which bounds the batch at
+ * T*k <= 1048576 assignments (MOE_EINVAL beyond that; also for E > 256, k > min(E,16), null pointers).  The
+ * call enqueues kernels only (no hipMalloc, no hipFree, no hipMemset) on hip_stream (NULL = default stream),
+ * on the current device.  Same outputs, bit for bit, as moe_route_replay.
+ *   id_flags: two ints of device memory owned by the caller, or NULL.  The call first clears them, then
+ *   id_flags[0] is set if an id lies outside [0,E) and id_flags[1] if an id repeats inside a token (with NULL
+ *   the flags go to the library's array and are not reported).
+ * Every call on one GPU uses the same array: calls that overlap on a GPU (different streams or threads) race;
+ * calls in stream order do not.  T == 0: only offsets[0..E] = 0 is written. */
+int moe_route_replay_noalloc(void* hip_stream, int32_t T, int32_t E, int32_t k,
+                             const int32_t* logged_idx, const float* logged_w,
+                             int32_t* topk_idx, float* topk_w, int32_t* offsets,
+                             int32_t* perm, int32_t* inv_perm, int32_t* id_flags);
+
 /* Ids-only Router Replay (section 2.4.4 read literally: the router's DECISIONS are reused).  The logged
  * expert ids are copied to topk_idx; the gate weights are recomputed from this engine's own logits,
  * topk_w[t,j] = softmax over logit[t, logged_idx[t,0..k-1]] (same logits, same arithmetic as moe_route, so

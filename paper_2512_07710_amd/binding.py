@@ -17,7 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libmoe355.so")
 _lib: Optional[ctypes.CDLL] = None
 
-EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_route_replay_ids",
+EXPORTS = ("moe_create", "moe_destroy", "moe_strerror", "moe_route", "moe_route_replay", "moe_route_replay_noalloc",
+           "moe_route_replay_ids",
            "moe_check_ids", "moe_quantize_fp8", "moe_quantize_weights_fp8", "moe_linear_fp8", "moe_expert_ffn_fp8",
            "moe_expert_ffn_fp8_gather", "moe_combine", "moe_balance_lengths", "moe_debug_copy_hidden",
            "moe_probe_copy", "moe_probe_fp8_mfma", "moe_profile_enable", "moe_profile_read", "moe_version")
@@ -51,6 +52,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_route.argtypes = [vp, vp, vp, vp, i32, vp, vp, vp, vp, vp]
     lib.moe_route_replay.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_route_replay_ids.argtypes = [vp] * 9
+    lib.moe_route_replay_noalloc.argtypes = [vp, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     lib.moe_check_ids.argtypes = [vp]
     lib.moe_quantize_weights_fp8.argtypes = [vp, vp, i64, i32, vp, vp]
     lib.moe_linear_fp8.argtypes = [vp, vp, vp, i32, i32, vp, vp, i32, vp]
@@ -118,6 +120,18 @@ def moe_route_replay(ctx, x, logged_idx, logged_w, topk_idx, topk_w, offsets, pe
                                            _ptr(topk_w, torch.float32), _ptr(offsets, torch.int32),
                                            _ptr(perm, torch.int32), _ptr(inv_perm, torch.int32)),
            "moe_route_replay")
+
+
+def moe_route_replay_noalloc(stream, T, E, k, logged_idx, logged_w, topk_idx, topk_w, offsets, perm, inv_perm,
+                             id_flags=None) -> None:
+    """`stream`: a torch.cuda.Stream or None for torch's current stream."""
+    s = stream if stream is not None else torch.cuda.current_stream()
+    i32 = torch.int32
+    _check(load_library().moe_route_replay_noalloc(ctypes.c_void_p(s.cuda_stream), T, E, k, _ptr(logged_idx, i32),
+                                                   _ptr(logged_w, torch.float32), _ptr(topk_idx, i32),
+                                                   _ptr(topk_w, torch.float32), _ptr(offsets, i32), _ptr(perm, i32),
+                                                   _ptr(inv_perm, i32), _ptr(id_flags, i32)),
+           "moe_route_replay_noalloc")
 
 
 def moe_check_ids(ctx) -> int:

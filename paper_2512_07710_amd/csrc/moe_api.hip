@@ -125,6 +125,13 @@ int moe_route_replay(moe_ctx* c, const uint16_t* x, const int32_t* logged_idx, c
     return hip_rc(launch_permute(perm_args(c, true), logged_idx, idx_copy, logged_w, w_copy, offsets, perm, inv_perm));
 }
 
+int moe_route_replay_noalloc(void* hip_stream, int32_t T, int32_t E, int32_t k, const int32_t* logged_idx,
+                             const float* logged_w, int32_t* topk_idx, float* topk_w, int32_t* offsets,
+                             int32_t* perm, int32_t* inv_perm, int32_t* id_flags) {
+    return route_replay_noalloc((hipStream_t)hip_stream, T, E, k, logged_idx, logged_w, topk_idx, topk_w, offsets, perm,
+                                inv_perm, id_flags);
+}
+
 int moe_route_replay_ids(moe_ctx* c, const uint16_t* x, const float* W_r, const int32_t* logged_idx,
                          int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm, int32_t* inv_perm) {
     if (!c) return MOE_EINVAL;

@@ -53,6 +53,10 @@ struct permute_args {
 };
 hipError_t launch_permute(const permute_args& a, const int32_t* ids_in, int32_t* ids_copy, const float* w_in,
                           float* w_copy, int32_t* offsets, int32_t* perm, int32_t* inv_perm);
+// Router Replay with every byte of workspace in a static device array (permute.hip)
+int route_replay_noalloc(hipStream_t stream, int32_t T, int32_t E, int32_t k, const int32_t* logged_idx,
+                         const float* logged_w, int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm,
+                         int32_t* inv_perm, int32_t* id_flags);
 hipError_t launch_probe_copy(hipStream_t stream, const void* src, void* dst, size_t bytes);
 hipError_t launch_probe_mfma(hipStream_t stream, int blocks, int steps, bool scaled, float* sink);
 hipError_t launch_fill_i32(hipStream_t stream, int32_t* p, int n, int32_t v);

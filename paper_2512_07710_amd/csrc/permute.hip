@@ -14,8 +14,41 @@
 // assignments take one fused launch instead (permute_one_chunk).
 #include "moe_internal.hpp"
 
+#include <mutex>
+
 namespace moe355 {
 namespace {
+
+// Scratch of moe_route_replay_noalloc: the per-chunk histograms of the three-kernel permutation, then two flag
+// words.  A file-scope device array (every GPU the library runs on holds its own copy until the process ends)
+// instead of a hipMalloc'ed workspace, so that the call allocates nothing.
+constexpr int NOALLOC_MAX_N = 1 << 20;                                  // assignments (T*k) per call
+constexpr int NOALLOC_COUNT_INTS = (NOALLOC_MAX_N / PERM_CHUNK) * MAX_E; // 512 chunks x 256 experts
+constexpr int NOALLOC_FLAG_INTS = 64;
+static __device__ __align__(256) int32_t scratch[NOALLOC_COUNT_INTS + NOALLOC_FLAG_INTS];   // 512.25 KiB
+
+// Host code never passes `scratch` itself to a kernel (there the name is a host-side stand-in): the device
+// address is asked for once per device and kept here.
+constexpr int MAX_DEVICES = 64;
+int32_t* scratch_addr[MAX_DEVICES] = {};
+std::mutex scratch_mutex;
+
+hipError_t scratch_on_current_device(int32_t** out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_addr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        scratch_addr[dev] = static_cast<int32_t*>(p);
+    }
+    *out = scratch_addr[dev];
+    return hipSuccess;
+}
 
 // Each of the four waves ranks a quarter of the chunk, 64 entries at a time: eight ballots (one per
 // bit of the expert id) give every lane the set of lanes that hold the same id, its rank among them is
@@ -254,6 +287,28 @@ hipError_t launch_permute(const permute_args& a, const int32_t* ids_in, int32_t*
         hipLaunchKernelGGL(scatter, dim3((N + 255) / 256), dim3(256), 0, a.stream, ids_in, N, a.E,
                            a.chunk_counts, offsets, w_in, w_copy, perm, inv_perm, a.k, a.check_dups, a.flags);
     return hipGetLastError();
+}
+
+// Router Replay (copy of the log + stable permutation) whose only workspace is the static device array above.
+// Overlapping calls on one GPU (two streams, two threads) share that array and race.
+int route_replay_noalloc(hipStream_t stream, int32_t T, int32_t E, int32_t k, const int32_t* logged_idx,
+                         const float* logged_w, int32_t* topk_idx, float* topk_w, int32_t* offsets, int32_t* perm,
+                         int32_t* inv_perm, int32_t* id_flags) {
+    if (T < 0 || E < 1 || E > MAX_E || k < 1 || k > E || k > MAX_K) return MOE_EINVAL;
+    if ((int64_t)T * k > NOALLOC_MAX_N) return MOE_EINVAL;             // beyond the scratch array's capacity
+    if (!offsets) return MOE_EINVAL;
+    if (T > 0 && (!logged_idx || !logged_w || !topk_idx || !topk_w || !perm || !inv_perm)) return MOE_EINVAL;
+    int32_t* base = nullptr;
+    if (scratch_on_current_device(&base) != hipSuccess) return MOE_EHIP;
+    int32_t* flags = id_flags ? id_flags : base + NOALLOC_COUNT_INTS;
+    // the flags must start at zero (the histograms need no clearing: every chunk in use is rewritten in full)
+    if (launch_fill_i32(stream, flags, 2, 0) != hipSuccess) return MOE_EHIP;
+    if (T == 0) return launch_fill_i32(stream, offsets, E + 1, 0) == hipSuccess ? MOE_OK : MOE_EHIP;
+    const permute_args a{stream, T, E, k, base, flags, true};
+    int32_t* idx_copy = (topk_idx == logged_idx) ? nullptr : topk_idx;
+    float* w_copy = (topk_w == logged_w) ? nullptr : topk_w;
+    return launch_permute(a, logged_idx, idx_copy, logged_w, w_copy, offsets, perm, inv_perm) == hipSuccess ? MOE_OK
+                                                                                                           : MOE_EHIP;
 }
 
 }  // namespace moe355
