@@ -69,6 +69,17 @@ def test_null_arguments_are_rejected(lib):
     assert lib.moe_combine(*([None] * 5)) == -1
     assert lib.moe_debug_copy_hidden(None, None, None) == -1
     assert lib.moe_check_ids(None) == -1
+    assert lib.moe_probe_copy(None, None, None, 1024) == -1
+    assert lib.moe_probe_fp8_mfma(None, 1, 1, 0, None) == -1
+
+
+def test_noalloc_replay_validates_before_touching_a_device(lib):
+    n = [None] * 8
+    assert lib.moe_route_replay_noalloc(None, 65537, 256, 16, *n) == -1     # T*k beyond the static scratch array
+    assert lib.moe_route_replay_noalloc(None, 10, 300, 2, *n) == -1         # more experts than supported
+    assert lib.moe_route_replay_noalloc(None, 10, 8, 9, *n) == -1           # k > E
+    assert lib.moe_route_replay_noalloc(None, -1, 8, 2, *n) == -1
+    assert lib.moe_route_replay_noalloc(None, 10, 8, 2, *n) == -1           # null arrays
 
 
 def test_binding_fails_loudly_without_library(tmp_path):
