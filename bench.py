@@ -183,6 +183,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=4, help="index into the five workloads (default: the largest)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-other-configs", action="store_true", help="skip the compact figures of configs 1-3")
+    ap.add_argument("--no-extensions", action="store_true",
+                    help="skip the entry points beyond the core calls and the ceiling probes (clean kernel traces)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus must be 1", file=sys.stderr)
@@ -278,23 +280,26 @@ def main() -> int:
         "stages_ms": stages,
         "kernels": kernels,
         "roofline": roof,
-        "ceilings": _ceilings(torch, moe, layer.ctx, dev),
+        "ceilings": None if args.no_extensions else _ceilings(torch, moe, layer.ctx, dev),
         "configs": others,
     }
     # the entry points beyond the five core calls, timed outside the headline region (same resident inputs)
     ext = {}
-    if "routed" in cfg.modes:
+    if args.no_extensions:
+        rows_l = rows_w = 0
+    elif "routed" in cfg.modes:
         ext["route_replay_ids_ms"] = _stage_ms(torch, lambda: layer.route_replay_ids(x, W_r, log_idx))
-    rows_w = min(cfg.E * F, 16 * 4096)                        # a slab of bf16 gate weights of 16*4096 rows
-    w_bf16 = torch.randn((rows_w, d), device=dev, dtype=torch.float32).mul_(d ** -0.5).to(torch.bfloat16)
-    wq = torch.empty((rows_w, d), dtype=torch.uint8, device=dev)
-    wsc = torch.empty((rows_w // 128, d // 128), dtype=torch.float32, device=dev)
-    t_wq = _stage_ms(torch, lambda: moe.moe_quantize_weights_fp8(layer.ctx, w_bf16, rows_w, d, wq, wsc))
-    ext["weight_quant_ms"] = t_wq
-    ext["weight_quant_GBs"] = 3.0 * rows_w * d / (t_wq * 1e-3) / 1e9
-    ext["weight_quant_frac_hbm"] = ext["weight_quant_GBs"] / HBM_PEAK_GBS
-    rows_l = min(8192, N)                                     # dense linear: [rows_l, d] x [rows_w, d]^T
-    if rows_l * rows_w <= N * d:                              # y_perm doubles as the output buffer
+    if not args.no_extensions:
+        rows_w = min(cfg.E * F, 16 * 4096)                    # a slab of bf16 gate weights of 16*4096 rows
+        w_bf16 = torch.randn((rows_w, d), device=dev, dtype=torch.float32).mul_(d ** -0.5).to(torch.bfloat16)
+        wq = torch.empty((rows_w, d), dtype=torch.uint8, device=dev)
+        wsc = torch.empty((rows_w // 128, d // 128), dtype=torch.float32, device=dev)
+        t_wq = _stage_ms(torch, lambda: moe.moe_quantize_weights_fp8(layer.ctx, w_bf16, rows_w, d, wq, wsc))
+        ext["weight_quant_ms"] = t_wq
+        ext["weight_quant_GBs"] = 3.0 * rows_w * d / (t_wq * 1e-3) / 1e9
+        ext["weight_quant_frac_hbm"] = ext["weight_quant_GBs"] / HBM_PEAK_GBS
+        rows_l = min(8192, N)                                 # dense linear: [rows_l, d] x [rows_w, d]^T
+    if rows_l and rows_l * rows_w <= N * d:                   # y_perm doubles as the output buffer
         xs_l = layer.xs[:, :rows_l].contiguous()
         t_lin = _stage_ms(torch, lambda: moe.moe_linear_fp8(layer.ctx, layer.xq, xs_l, rows_l, d, wq, wsc, rows_w,
                                                             layer.y_perm), reps=5)
@@ -302,7 +307,6 @@ def main() -> int:
         ext["dense_linear_tflops"] = 2.0 * rows_l * d * rows_w / (t_lin * 1e-3) / 1e12
         ext["dense_linear_shape"] = [rows_l, d, rows_w]
     out["extensions"] = ext
-    del w_bf16, wq, wsc
     if not args.no_cpu_baseline:
         Ts, Es = min(1024, T), min(8, cfg.E)
         ks = min(k, Es)

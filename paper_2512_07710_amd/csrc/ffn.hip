@@ -84,13 +84,18 @@ __global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ of
         // Down projection: experts with three or more tiles whose remainder is at most 128 rows get full tiles
         // plus one short tile: a short tile keeps half of the block's waves out of the matrix work and,
         // measured, costs 0.7 to 0.9 of a full one, less than making every tile of the expert ragged.
-        // Otherwise, and always in the gate/up projection, tile i covers rows [i*cnt/nt, (i+1)*cnt/nt): the
-        // tiles that share a weight tile then advance in step and fetch it once (in the gate/up projection a
-        // short tile runs ahead of its neighbours and the weight tile is fetched twice: 13 GB more L2 misses
-        // at 256 experts x 1024 rows for no gain in time).
+        // Otherwise, and always in the gate/up projection, the expert's G = ceil(cnt/64) groups of 64 rows (the
+        // share of one wave pair) are dealt out evenly: tile i covers groups [i*G/nt, (i+1)*G/nt).  The tiles
+        // that share a weight tile then advance in step and fetch it once (in the gate/up projection a short tile
+        // runs ahead of its neighbours and the weight tile is fetched twice: 13 GB more L2 misses at 256 experts
+        // x 1024 rows for no gain in time), and only the expert's last group is partly filled: splitting the ROWS
+        // evenly instead leaves a partly filled group in every tile, whose wave pair does a full group's matrix
+        // work (3 % of the gate/up projection at 896..1152 rows per expert: the kernel runs at the power cap, so
+        // matrix work that is thrown away costs time even where it hides behind other waves).
         const bool short_tail = blockIdx.y == 1 && nt >= 3 && cnt - (nt - 1) * TOK_TILE <= TOK_TILE / 2;
-        const int lo = short_tail ? i * TOK_TILE : (int)((int64_t)i * cnt / nt);
-        const int hi = short_tail ? min(cnt, lo + TOK_TILE) : (int)((int64_t)(i + 1) * cnt / nt);
+        const int G = (cnt + 63) / 64;
+        const int lo = short_tail ? i * TOK_TILE : min(cnt, 64 * (int)((int64_t)i * G / nt));
+        const int hi = short_tail ? min(cnt, lo + TOK_TILE) : min(cnt, 64 * (int)((int64_t)(i + 1) * G / nt));
         Work w;
         w.expert = e;
         w.row0 = start + lo;

@@ -15,6 +15,8 @@
 // candidates, applies the softmax over the k selected unbiased logits and writes out.
 #include "moe_internal.hpp"
 
+#include <type_traits>
+
 namespace moe355 {
 namespace {
 
@@ -221,6 +223,16 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
 #pragma unroll
     for (int i = 0; i < AH; ++i) load_a(i, i);                 // nk >= 8 >= AH: d is a multiple of 128
 
+    // activation operands of one K step: TS reads of 16 bytes per lane from the staged chunk
+    auto read_b = [&](v4i (&b)[TS], const uint8_t* stage, int ks) {
+#pragma unroll
+        for (int ts = 0; ts < TS; ++ts) {
+            const int row = ts * 32 + l32;
+            b[ts] = *reinterpret_cast<const v4i*>(stage + (ks >> 2) * RT * 128 + row * 128 +
+                                                  ((((ks & 3) * 2 + half) ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
+        }
+    };
+    v4i b[2][TS];                                              // step ks multiplies out of b[ks & 1] while b[(ks+1) & 1] loads
     for (int kc = 0; kc < nchunks; ++kc) {
         // chunk kc must have landed.  Vector-memory operations complete in issue order: after the copies
         // of chunk kc this wave has issued exactly KS K steps of weight loads (L each), except
@@ -229,17 +241,14 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
         __syncthreads();                                       // landed for everybody; chunk kc-1 fully consumed
         if (kc + 1 < nchunks) issue_x(kc + 1);
         const uint8_t* stage = smem + (kc & 1) * STAGE;
+        read_b(b[0], stage, 0);
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) {
             const int kk = kc * KS + ks;
             if (kk + AH < nk) load_a((ks + AH) % KS, kk + AH);
-            v4i b[TS];
-#pragma unroll
-            for (int ts = 0; ts < TS; ++ts) {
-                const int row = ts * 32 + l32;
-                b[ts] = *reinterpret_cast<const v4i*>(stage + (ks >> 2) * RT * 128 + row * 128 +
-                                                      ((((ks & 3) * 2 + half) ^ (row & 7) ^ ((row >> 3) & 1)) << 4));
-            }
+            // the next step's activation operands (same chunk: the last step of a chunk has none to fetch, the
+            // next chunk's first operands are read behind the barrier above)
+            if (ks + 1 < KS) read_b(b[(ks + 1) & 1], stage, ks + 1);
             // The weight operands of this K step were requested AH steps ago; vector-memory operations
             // complete in issue order, so "at most as many outstanding as were issued since" means they
             // have arrived.  (Written out by hand: the steady-state loop gets no automatic wait for
@@ -253,6 +262,10 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
             } else {
                 WAIT_VM((KS - 1 - ks) * L);
             }
+            // this step's activation operands were requested one step ago: all LDS reads but the TS just issued
+            // must have returned (the compiler cannot see this through the asm below, so it is written out)
+            if (ks + 1 < KS) asm volatile("s_waitcnt lgkmcnt(%0)" :: "n"(TS) : "memory");
+            else asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
             for (int s = 0; s < NS; ++s)
 #pragma unroll
@@ -260,7 +273,7 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
 #pragma unroll
                     for (int ts = 0; ts < TS; ++ts)
                         asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0"
-                                     : "+a"(acc[s][ts]) : "v"(a[ks][s][p]), "v"(b[ts]) : "memory");
+                                     : "+a"(acc[s][ts]) : "v"(a[ks][s][p]), "v"(b[ks & 1][ts]) : "memory");
         }
     }
     // the last matrix instructions must have left the pipe before the accumulators are read
@@ -290,66 +303,87 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
         }
         __syncthreads();
         if (tid < RT && t0 + tid < T) {
+            // loops over MAX_K slots with a compile-time index (slots >= k are skipped), so that the selected logits
+            // stay in registers: an array indexed by a run-time j would live in scratch memory
             const int32_t* ids = logged_idx + (size_t)(t0 + tid) * k;
             float lg[MAX_K];
             float m = -INFINITY;
-            for (int j = 0; j < k; ++j) { lg[j] = sel[tid * MAX_K + j]; m = fmaxf(m, lg[j]); }
+#pragma unroll
+            for (int j = 0; j < MAX_K; ++j)
+                if (j < k) { lg[j] = sel[tid * MAX_K + j]; m = fmaxf(m, lg[j]); }
             float sum = 0.f;
-            for (int j = 0; j < k; ++j) { lg[j] = expf(lg[j] - m); sum += lg[j]; }
-            for (int j = 0; j < k; ++j) {
-                topk_idx[(size_t)(t0 + tid) * k + j] = ids[j];
-                topk_w[(size_t)(t0 + tid) * k + j] = lg[j] / sum;
-            }
+#pragma unroll
+            for (int j = 0; j < MAX_K; ++j)
+                if (j < k) { lg[j] = expf(lg[j] - m); sum += lg[j]; }
+#pragma unroll
+            for (int j = 0; j < MAX_K; ++j)
+                if (j < k) {
+                    topk_idx[(size_t)(t0 + tid) * k + j] = ids[j];
+                    topk_w[(size_t)(t0 + tid) * k + j] = lg[j] / sum;
+                }
         }
         return;
     }
 
     // ---- per-wave top-k.  Lane (l32, half) holds, for token ts*32+l32, the logits of experts
-    //      wave*32*NS + s*32 + (r/4)*8 + half*4 + (r%4).  Candidates: cand[token][wave][j] = {logit, idx}
+    //      wave*32*NS + s*32 + (r/4)*8 + half*4 + (r%4), position pos = s*16 + r (ascending in the expert index).
+    //      Candidates: cand[token][wave][j] = {logit, idx}.
+    //      The selection scores (logit + bias; -inf for padded experts) are copied to vector registers once - the
+    //      weight ring's registers are free by now - and a taken score is overwritten with -inf, so that a round is
+    //      one scan "strictly larger wins" (3 instructions per score: ties keep the lower index) and one marking pass
+    //      (2 per score), which with a bias also picks the winner's unbiased logit out of the accumulators.
     float2* cand = reinterpret_cast<float2*>(smem);
-    uint32_t taken[TS];                                        // bit (s*16 + r)
+    float sc[NS][TS][16];
 #pragma unroll
-    for (int ts = 0; ts < TS; ++ts) taken[ts] = 0u;
+    for (int s = 0; s < NS; ++s)
 #pragma unroll
-    for (int ts = 0; ts < TS; ++ts) {
+        for (int r = 0; r < 16; ++r) {
+            const int e = (wave * NS + s) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+            const float be = bias ? bias[min(e, E - 1)] : 0.f;
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
+            for (int ts = 0; ts < TS; ++ts) sc[s][ts][r] = e < E ? acc[s][ts][r] + be : -INFINITY;
+        }
+    auto extract = [&](auto with_bias) {
+        constexpr bool WB = decltype(with_bias)::value;
+        for (int j = 0; j < k; ++j) {
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int e = (wave * NS + s) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                if (e >= E) taken[ts] |= 1u << (s * 16 + r);
-            }
-    }
-    for (int j = 0; j < k; ++j) {
+            for (int ts = 0; ts < TS; ++ts) {
+                float bs = -INFINITY;
+                int bpos = -1;
 #pragma unroll
-        for (int ts = 0; ts < TS; ++ts) {
-            float bs = 0.f, bl = 0.f;
-            int bi = NO_CAND, bpos = 0;
+                for (int s = 0; s < NS; ++s)
 #pragma unroll
-            for (int s = 0; s < NS; ++s)
+                    for (int r = 0; r < 16; ++r) {
+                        const float v = sc[s][ts][r];
+                        if (v > bs) { bs = v; bpos = s * 16 + r; }
+                    }
+                const int bi = bpos < 0 ? NO_CAND
+                                        : (wave * NS + (bpos >> 4)) * 32 + ((bpos & 15) >> 2) * 8 + half * 4 + (bpos & 3);
+                // the partner lane holds the other half of the wave's experts for the same token
+                const float os = __shfl_xor(bs, 32);
+                const int oi = __shfl_xor(bi, 32);
+                const bool mine = bi != NO_CAND && (oi == NO_CAND || bs > os || (bs == os && bi < oi));
+                const int mark = mine ? bpos : -1;
+                float bl = bs;                                 // without a bias the score is the logit
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    // ascending expert index within the lane: (r>>2) major, (r&3) minor, s outermost
-                    const int e = (wave * NS + s) * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-                    const float lg = acc[s][ts][r];
-                    const float sc = lg + (bias ? bias[min(e, E - 1)] : 0.f);
-                    const bool free_ = !((taken[ts] >> (s * 16 + r)) & 1u);
-                    if (free_ && (bi == NO_CAND || sc > bs)) { bs = sc; bl = lg; bi = e; bpos = s * 16 + r; }
+                for (int s = 0; s < NS; ++s)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const bool hit = mark == s * 16 + r;
+                        if (WB && hit) bl = acc[s][ts][r];
+                        sc[s][ts][r] = hit ? -INFINITY : sc[s][ts][r];
+                    }
+                const float ol = __shfl_xor(bl, 32);
+                if (half == 0) {
+                    float2 c;
+                    c.x = mine ? bl : ol;
+                    c.y = __int_as_float(mine ? bi : oi);
+                    cand[((ts * 32 + l32) * 4 + wave) * MAX_K + j] = c;
                 }
-            // the partner lane holds the other half of the wave's experts for the same token
-            const float os = __shfl_xor(bs, 32);
-            const float ol = __shfl_xor(bl, 32);
-            const int oi = __shfl_xor(bi, 32);
-            const bool mine = bi != NO_CAND && (oi == NO_CAND || bs > os || (bs == os && bi < oi));
-            if (mine) taken[ts] |= 1u << bpos;
-            if (half == 0) {
-                float2 c;
-                c.x = mine ? bl : ol;
-                c.y = __int_as_float(mine ? bi : oi);
-                cand[((ts * 32 + l32) * 4 + wave) * MAX_K + j] = c;
             }
         }
-    }
+    };
+    if (bias) extract(std::true_type{}); else extract(std::false_type{});
     __syncthreads();
 
     // ---- merge the four waves' candidates, softmax, store: one thread per token.  Every wave's list is already in
@@ -357,10 +391,13 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     if (tid < RT && t0 + tid < T) {
         const float2* mine = cand + (size_t)tid * 4 * MAX_K;
         int head0 = 0, head1 = 0, head2 = 0, head3 = 0;
+        // slots are walked with a compile-time index (those >= k are skipped): the selected logits and ids stay in
+        // registers, where an array indexed by a run-time j would live in scratch memory
         float sel_logit[MAX_K];
-        int sel_idx[MAX_K];
         float m = -INFINITY;
-        for (int j = 0; j < k; ++j) {
+#pragma unroll
+        for (int j = 0; j < MAX_K; ++j) {
+            if (j >= k) continue;
             float bs = 0.f, bl = 0.f;
             int bi = NO_CAND, bw = 0;
 #pragma unroll
@@ -375,15 +412,16 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
             }
             head0 += bw == 0; head1 += bw == 1; head2 += bw == 2; head3 += bw == 3;
             sel_logit[j] = bl;
-            sel_idx[j] = bi;
+            topk_idx[(size_t)(t0 + tid) * k + j] = bi;
             m = fmaxf(m, bl);
         }
         float sum = 0.f;
-        for (int j = 0; j < k; ++j) { sel_logit[j] = expf(sel_logit[j] - m); sum += sel_logit[j]; }
-        for (int j = 0; j < k; ++j) {
-            topk_idx[(size_t)(t0 + tid) * k + j] = sel_idx[j];
-            topk_w[(size_t)(t0 + tid) * k + j] = sel_logit[j] / sum;
-        }
+#pragma unroll
+        for (int j = 0; j < MAX_K; ++j)
+            if (j < k) { sel_logit[j] = expf(sel_logit[j] - m); sum += sel_logit[j]; }
+#pragma unroll
+        for (int j = 0; j < MAX_K; ++j)
+            if (j < k) topk_w[(size_t)(t0 + tid) * k + j] = sel_logit[j] / sum;
     }
 }
 
