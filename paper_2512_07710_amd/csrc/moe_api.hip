@@ -70,6 +70,8 @@ int moe_create(moe_ctx** out, const moe_dims* dims, void* hip_stream) {
     ok = ok && hipMalloc((void**)&c->n_tiles, 4 * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->flags, 4 * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->router_planes, route_workspace_bytes(dims->E, dims->d)) == hipSuccess;
+    if (route_partial_bytes(dims->T, dims->E))
+        ok = ok && hipMalloc((void**)&c->route_partial, route_partial_bytes(dims->T, dims->E)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->xs_sorted, nrow * (size_t)(dims->d / QBLOCK) * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hq, nrow * (size_t)dims->F) == hipSuccess;
     ok = ok && hipMalloc((void**)&c->hs, nrow * (size_t)(dims->F / QBLOCK) * sizeof(float)) == hipSuccess;
@@ -93,6 +95,7 @@ int moe_destroy(moe_ctx* c) {
     if (c->flags) (void)hipFree(c->flags);
     if (c->xs_sorted) (void)hipFree(c->xs_sorted);
     if (c->router_planes) (void)hipFree(c->router_planes);
+    if (c->route_partial) (void)hipFree(c->route_partial);
     if (c->hq) (void)hipFree(c->hq);
     if (c->hs) (void)hipFree(c->hs);
     if (c->prof_events) {

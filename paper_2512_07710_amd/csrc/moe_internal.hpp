@@ -29,6 +29,7 @@ struct moe_ctx {
                              //     inside a token; [2..3]: row range of a dense linear
     float* xs_sorted;        // [d/128][N] activation scales in sorted order (gathered FFN only)
     uint16_t* router_planes; // router weights split into three bf16 planes, matrix-core order
+    float* route_partial;    // [splits][T padded to 32][E padded] partial logits of the split router (small batches only)
     uint8_t* hq;             // [N][F]
     float* hs;               // [N][F/128]
     // optional kernel timing: three events per recorded expert-FFN call
@@ -71,6 +72,7 @@ hipError_t launch_quantize_weights(hipStream_t s, const uint16_t* w, int64_t row
                                    float* scales);
 size_t ffn_work_bytes(int max_tiles, int F, int d);
 size_t route_workspace_bytes(int E, int d);
+size_t route_partial_bytes(int T, int E);
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm,
                           const float* topk_w, uint16_t* y);
 

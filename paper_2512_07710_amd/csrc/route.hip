@@ -148,13 +148,17 @@ __device__ inline void wait_vm(int n) {
 // with 4 the K loop of the small token tiles is a chain of L2 round trips).
 // IDS = false: top-k selection.  IDS = true (ids-only Router Replay): the k expert ids of every token are
 // given in logged_idx; their logits are picked out of the same accumulators and only the softmax is new.
-template <int NS, int TS, int KS, bool IDS>
+// SPLIT = true (small batches, where one block per token tile would leave most compute units idle): block
+// (x, y) runs only chunks [y*cps, (y+1)*cps) of the K loop and writes its partial logits to
+// partial[y][token][expert]; route_finish_kernel adds the partials up and does the selection.
+template <int NS, int TS, int KS, bool IDS, bool SPLIT = false>
 __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __restrict__ x,
                                                             const uint16_t* __restrict__ planes,
                                                             const float* __restrict__ bias,
                                                             const int32_t* __restrict__ logged_idx, int T, int d,
                                                             int E, int k, int32_t* __restrict__ topk_idx,
-                                                            float* __restrict__ topk_w) {
+                                                            float* __restrict__ topk_w,
+                                                            float* __restrict__ partial, int cps) {
     constexpr int RT = 32 * TS;                                // tokens per block
     constexpr int PANELS = KS / 4;                             // a chunk is staged as panels of RT rows x 128 bytes (64 columns)
     constexpr int STAGE = PANELS * RT * 128;                   // bytes of one staged chunk
@@ -171,7 +175,10 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, half = lane >> 5;
     const int t0 = blockIdx.x * RT;
-    const int nk = d / 16, nchunks = nk / KS;
+    const int nchunks_all = d / (16 * KS);
+    const int kc_begin = SPLIT ? (int)blockIdx.y * cps : 0;
+    const int nchunks = SPLIT ? min(nchunks_all, kc_begin + cps) : nchunks_all;   // this block's chunks: [kc_begin, nchunks)
+    const int nk = nchunks * KS;                                                  // one past its last K step
 
     // activation staging by direct-to-LDS copies: wave w, copy j < TS brings rows (TS*w+j)*8 .. +7 of the chunk;
     // lane i -> row i/8, LDS chunk slot i%8, which receives global 16-byte chunk
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     const v4i* wsrc[NS];
 #pragma unroll
     for (int s = 0; s < NS; ++s)
-        wsrc[s] = reinterpret_cast<const v4i*>(planes) + ((size_t)(wave * NS + s) * nk * 3) * 64 + lane;
+        wsrc[s] = reinterpret_cast<const v4i*>(planes) + ((size_t)(wave * NS + s) * (d / 16) * 3) * 64 + lane;
 
     // accumulators live in the accumulation registers for the whole K loop; the matrix instructions are
     // volatile asm with a memory clobber, so they and the loads around them stay in source order
@@ -219,9 +226,9 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
 #pragma unroll
             for (int p = 0; p < 3; ++p) a[slot][s][p] = wsrc[s][((size_t)kk * 3 + p) * 64];
     };
-    issue_x(0);
+    issue_x(kc_begin);
 #pragma unroll
-    for (int i = 0; i < AH; ++i) load_a(i, i);                 // nk >= 8 >= AH: d is a multiple of 128
+    for (int i = 0; i < AH; ++i) load_a(i, kc_begin * KS + i);   // a block has at least one chunk = KS > AH steps
 
     // activation operands of one K step: TS reads of 16 bytes per lane from the staged chunk
     auto read_b = [&](v4i (&b)[TS], const uint8_t* stage, int ks) {
@@ -233,11 +240,11 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
         }
     };
     v4i b[2][TS];                                              // step ks multiplies out of b[ks & 1] while b[(ks+1) & 1] loads
-    for (int kc = 0; kc < nchunks; ++kc) {
+    for (int kc = kc_begin; kc < nchunks; ++kc) {
         // chunk kc must have landed.  Vector-memory operations complete in issue order: after the copies
         // of chunk kc this wave has issued exactly KS K steps of weight loads (L each), except
         // before the first chunk.
-        if (kc == 0) WAIT_VM(0); else WAIT_VM(KS * L);
+        if (kc == kc_begin) WAIT_VM(0); else WAIT_VM(KS * L);
         __syncthreads();                                       // landed for everybody; chunk kc-1 fully consumed
         if (kc + 1 < nchunks) issue_x(kc + 1);
         const uint8_t* stage = smem + (kc & 1) * STAGE;
@@ -279,6 +286,23 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     // the last matrix instructions must have left the pipe before the accumulators are read
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __syncthreads();                                           // all reads of the activation stages are done
+
+    if (SPLIT) {
+        // partial[y][t][e], t over the padded token tiles, e over the padded experts: a lane owns four consecutive experts
+        const int T_pad = gridDim.x * RT, E_pad = 128 * NS;
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+#pragma unroll
+            for (int ts = 0; ts < TS; ++ts)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int e = (wave * NS + s) * 32 + r4 * 8 + half * 4;
+                    const size_t at = ((size_t)blockIdx.y * T_pad + t0 + ts * 32 + l32) * E_pad + e;
+                    *reinterpret_cast<float4*>(partial + at) = make_float4(acc[s][ts][r4 * 4], acc[s][ts][r4 * 4 + 1],
+                                                                           acc[s][ts][r4 * 4 + 2], acc[s][ts][r4 * 4 + 3]);
+                }
+        return;
+    }
 
     if (IDS) {
         // every lane looks up the logged ids of its TS tokens among the experts it holds
@@ -425,11 +449,88 @@ __global__ __launch_bounds__(256, 1) void route_mfma_kernel(const uint16_t* __re
     }
 }
 
+// Second half of the split router: one wave per token adds the partial logits up in split order, then
+// selects as the single-pass kernel does (larger score, then lower expert index; softmax over the k selected
+// unbiased logits, exponentials summed in slot order) or, with logged ids, picks their logits.  Lane l holds
+// experts l, l+64, l+128, l+192.
+template <bool IDS>
+__global__ __launch_bounds__(256) void route_finish_kernel(const float* __restrict__ partial, int splits, int T_pad,
+                                                           int E_pad, const float* __restrict__ bias,
+                                                           const int32_t* __restrict__ logged_idx, int T, int E, int k,
+                                                           int32_t* __restrict__ topk_idx, float* __restrict__ topk_w) {
+    const int lane = threadIdx.x & 63;
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= T) return;                                        // wave-uniform
+    float lg[4], sc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int e = lane + 64 * i;
+        float v = 0.f;
+        if (e < E_pad)
+            for (int sp = 0; sp < splits; ++sp) v += partial[((size_t)sp * T_pad + t) * E_pad + e];
+        lg[i] = v;
+        sc[i] = e < E ? v + (bias ? bias[e] : 0.f) : -INFINITY;
+    }
+    float sel = 0.f;                                           // lane j < k: the j-th selected logit
+    for (int j = 0; j < k; ++j) {
+        int be;
+        if (IDS) {
+            be = logged_idx[(size_t)t * k + j];
+        } else {
+            float bs = -INFINITY;
+            be = NO_CAND;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (sc[i] > bs) { bs = sc[i]; be = lane + 64 * i; }       // ascending index: ties keep the lower one
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const float os = __shfl_xor(bs, off);
+                const int oe = __shfl_xor(be, off);
+                if (os > bs || (os == bs && oe < be)) { bs = os; be = oe; }
+            }
+        }
+        const bool valid = be >= 0 && be < E;                  // wave-uniform (ids outside [0,E) keep logit 0)
+        const int slot = valid ? be >> 6 : 0;
+        const float mine = slot == 0 ? lg[0] : slot == 1 ? lg[1] : slot == 2 ? lg[2] : lg[3];
+        const float chosen = valid ? __shfl(mine, be & 63) : 0.f;
+        if (!IDS && valid && lane == (be & 63)) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (i == slot) sc[i] = -INFINITY;
+        }
+        if (lane == j) sel = chosen;
+        if (lane == 0) topk_idx[(size_t)t * k + j] = be;
+    }
+    float m = -INFINITY;
+    for (int j = 0; j < k; ++j) m = fmaxf(m, __shfl(sel, j));
+    float sum = 0.f;
+    for (int j = 0; j < k; ++j) sum += expf(__shfl(sel, j) - m);
+    if (lane < k) topk_w[(size_t)t * k + lane] = expf(sel - m) / sum;
+}
+
 }  // namespace
 
 size_t route_workspace_bytes(int E, int d) {
     const int E_pad = E <= 128 ? 128 : 256;
     return (size_t)3 * E_pad * d * sizeof(uint16_t);
+}
+
+// Batches of at most ROUTE_SPLIT_MAX_T tokens (fewer 32-token tiles than half the compute units) run the K loop
+// split over up to ROUTE_MAX_SPLITS blocks per token tile: as many as bring the grid to about 256 blocks.
+constexpr int ROUTE_SPLIT_MAX_T = 4096;
+constexpr int ROUTE_MAX_SPLITS = 16;
+
+static int route_splits_for(int T) {
+    const int tiles = (T + 31) / 32;
+    const int s = 256 / tiles;
+    return s < 1 ? 1 : s > ROUTE_MAX_SPLITS ? ROUTE_MAX_SPLITS : s;
+}
+
+size_t route_partial_bytes(int T, int E) {
+    if (T < 1 || T > ROUTE_SPLIT_MAX_T || route_splits_for(T) < 2) return 0;
+    const int E_pad = E <= 128 ? 128 : 256;
+    const size_t T_pad = (size_t)((T + 31) / 32) * 32;
+    return (size_t)route_splits_for(T) * T_pad * E_pad * sizeof(float);
 }
 
 hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const float* bias,
@@ -440,12 +541,36 @@ hipError_t launch_route(moe_ctx* c, const uint16_t* x, const float* W_r, const f
     const int64_t nthreads = (int64_t)E_pad * (D.d / 8);
     hipLaunchKernelGGL(split_router_weights, dim3((unsigned)((nthreads + 255) / 256)), dim3(256), 0, c->stream,
                        W_r, D.E, E_pad, D.d, c->router_planes);
+    const int nchunks = D.d / 128;
+    if (D.T <= ROUTE_SPLIT_MAX_T && c->route_partial && nchunks >= 2) {
+        // small batch: 32-token tiles, the K loop of each split over enough blocks to occupy the chip
+        const int tiles = (D.T + 31) / 32;
+        int splits = route_splits_for(D.T);
+        const int cps = (nchunks + splits - 1) / splits;       // chunks per block
+        splits = (nchunks + cps - 1) / cps;                    // no empty block
+        if (splits >= 2) {
+            const dim3 grid(tiles, splits);
+#define MOE_ROUTE_SPLIT(NS_)                                                                                       \
+    hipLaunchKernelGGL((route_mfma_kernel<NS_, 1, 8, false, true>), grid, dim3(256), 0, c->stream, x, c->router_planes, \
+                       bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w, c->route_partial, cps)
+            if (E_pad == 128) MOE_ROUTE_SPLIT(1); else MOE_ROUTE_SPLIT(2);
+#undef MOE_ROUTE_SPLIT
+            const dim3 fgrid((D.T + 3) / 4);
+            if (logged_idx)
+                hipLaunchKernelGGL(route_finish_kernel<true>, fgrid, dim3(256), 0, c->stream, c->route_partial, splits,
+                                   tiles * 32, E_pad, (const float*)nullptr, logged_idx, D.T, D.E, D.k, topk_idx, topk_w);
+            else
+                hipLaunchKernelGGL(route_finish_kernel<false>, fgrid, dim3(256), 0, c->stream, c->route_partial, splits,
+                                   tiles * 32, E_pad, bias, logged_idx, D.T, D.E, D.k, topk_idx, topk_w);
+            return hipGetLastError();
+        }
+    }
     // token tile: the largest of 128 / 64 / 32 rows that still gives every compute unit a block
     const int TS = D.T >= 256 * 128 ? 4 : D.T >= 256 * 64 ? 2 : 1;
     const int grid = (D.T + 32 * TS - 1) / (32 * TS);
 #define MOE_ROUTE_LAUNCH(NS_, TS_, IDS_)                                                                    \
     hipLaunchKernelGGL((route_mfma_kernel<NS_, TS_, 8, IDS_>), dim3(grid), dim3(256), 0, c->stream, x,         \
-                       c->router_planes, bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w)
+                       c->router_planes, bias, logged_idx, D.T, D.d, D.E, D.k, topk_idx, topk_w, (float*)nullptr, 0)
 #define MOE_ROUTE_TS(NS_, IDS_)                                                                             \
     do {                                                                                                    \
         if (TS == 4) MOE_ROUTE_LAUNCH(NS_, 4, IDS_);                                                        \
