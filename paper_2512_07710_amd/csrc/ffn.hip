@@ -44,6 +44,7 @@ constexpr int NW_BUF = 3, NX_BUF = 2;              // LDS ring depths
 constexpr int X_RING = NW_BUF * W_TILE;            // byte offset of the activation ring
 constexpr int NTHREADS = 512;
 constexpr int NXCD = 8;
+constexpr int NARROW_ROWS = 64;                     // tiles of at most this many rows take the narrow path of ffn_gemm
 
 struct Work { int32_t expert; int32_t row0; int32_t ft; int32_t nrows; };
 
@@ -86,12 +87,14 @@ __global__ __launch_bounds__(256) void build_work(const int32_t* __restrict__ of
         // measured, costs 0.7 to 0.9 of a full one, less than making every tile of the expert ragged.
         // Otherwise, and always in the gate/up projection, the expert's G = ceil(cnt/64) groups of 64 rows (the
         // share of one wave pair) are dealt out evenly: tile i covers groups [i*G/nt, (i+1)*G/nt).  The tiles
-        // that share a weight tile then advance in step and fetch it once (in the gate/up projection a short tile
-        // runs ahead of its neighbours and the weight tile is fetched twice: 13 GB more L2 misses at 256 experts
-        // x 1024 rows for no gain in time), and only the expert's last group is partly filled: splitting the ROWS
-        // evenly instead leaves a partly filled group in every tile, whose wave pair does a full group's matrix
-        // work (3 % of the gate/up projection at 896..1152 rows per expert: the kernel runs at the power cap, so
-        // matrix work that is thrown away costs time even where it hides behind other waves).
+        // that share a weight tile then advance in step and fetch it once, and only the expert's last group is partly
+        // filled: splitting the ROWS evenly instead leaves a partly filled group in every tile, whose wave pair does a
+        // full group's matrix work (3 % of the gate/up projection at 896..1152 rows per expert: the kernel runs at
+        // the power cap, so matrix work that is thrown away costs time even where it hides behind other waves).
+        // A tile that runs faster than the tiles it shares a weight tile with does not pay: it runs ahead and the
+        // weight tile is fetched twice.  Measured for a remainder of at most 64 rows cut off as a NARROW tile (a fifth
+        // of a full tile's time by itself): gate/up projection 8 % slower at 248..264 rows per expert, 3 % slower at
+        // 896..1152.  Narrow tiles therefore arise only where an expert has at most 64 rows altogether.
         const bool short_tail = blockIdx.y == 1 && nt >= 3 && cnt - (nt - 1) * TOK_TILE <= TOK_TILE / 2;
         const int G = (cnt + 63) / 64;
         const int lo = short_tail ? i * TOK_TILE : min(cnt, 64 * (int)((int64_t)i * G / nt));
@@ -189,16 +192,24 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     //      LDS chunk slot i%8 which receives global chunk slot ^ (row & 7) ^ ((row >> 3) & 1): with that
     //      swizzle the 32-row x 16-byte operand reads below touch all 64 LDS banks evenly.
     //      Staged weight row r: GATED: features f0 + (r/128)*64 + r%64, gate (Wa) if (r/64)%2 == 0 else up (Wb).
-    const uint8_t* w_base;                                     // wave-uniform
+    //      NARROW tiles (at most 64 rows, see below): wave w's 32 staged rows are 32 consecutive features of the tile
+    //      (down projection) or, GATED, [16 gate rows | 16 up rows] of features f0 + 16w .. 16w+15.
+    const bool narrow = wk.nrows <= NARROW_ROWS;               // block-uniform
+    const uint8_t* w_base[2];                                  // wave-uniform: matrix of copy instructions 0,1 and 2,3
     uint32_t w_off[4], x_off[4];
     {
         const int sub = lane >> 3, cslot = lane & 7;
-        const uint8_t* wmat = (GATED && ((wave >> 1) & 1)) ? Wb : Wa;
-        w_base = wmat + (size_t)e * NOUT * (size_t)K;
+        const size_t we = (size_t)e * NOUT * (size_t)K;
+        if (GATED && narrow) {
+            w_base[0] = Wa + we;
+            w_base[1] = Wb + we;
+        } else {
+            w_base[0] = w_base[1] = ((GATED && ((wave >> 1) & 1)) ? Wb : Wa) + we;
+        }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int r = wave * 32 + j * 8 + sub;
-            int f = GATED ? f0 + (r >> 7) * 64 + (r & 63) : f0 + r;
+            int f = GATED ? (narrow ? f0 + wave * 16 + ((j * 8 + sub) & 15) : f0 + (r >> 7) * 64 + (r & 63)) : f0 + r;
             f = min(f, NOUT - 1);
             w_off[j] = (uint32_t)f * (uint32_t)K + ((cslot ^ (r & 7) ^ ((r >> 3) & 1)) << 4);
             const int p = min(wk.row0 + r, row_end - 1);      // rows past the tile repeat its last row
@@ -211,15 +222,13 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     const uint32_t lds_rows = lds0 + wave * 32 * KB;           // this wave's rows inside a tile buffer
 
     auto issue_w = [&](int kb, int wslot) {
-        const uint8_t* src = w_base + (size_t)kb * KB;
         const uint32_t dst = lds_rows + wslot * W_TILE;
 #pragma unroll
-        for (int j = 0; j < 4; ++j) dma16(dst + j * 8 * KB, w_off[j], src);
+        for (int j = 0; j < 4; ++j) dma16(dst + j * 8 * KB, w_off[j], w_base[j >> 1] + (size_t)kb * KB);
     };
     auto issue_w1 = [&](int kb, int wslot, int j) {
-        const uint8_t* src = w_base + (size_t)kb * KB;
         const uint32_t dst = lds_rows + wslot * W_TILE;
-        dma16(dst + j * 8 * KB, w_off[j], src);
+        dma16(dst + j * 8 * KB, w_off[j], w_base[j >> 1] + (size_t)kb * KB);
     };
     // 8-row activation copies that lie wholly beyond the expert's last row are not issued at all
     // (a ragged last tile then moves only the rows it has); wave-uniform
@@ -238,7 +247,7 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     };
 
     // ---- weight scales of this wave's rows (wave-uniform -> scalar loads)
-    const int blk_a = GATED ? wk.ft : min(wk.ft * 2 + wf, nblk_out - 1);
+    const int blk_a = GATED ? wk.ft : min(wk.ft * 2 + (narrow ? wave >> 2 : wf), nblk_out - 1);
     const float* sa_e = sa + ((size_t)e * nblk_out + blk_a) * nkb;
     const float* sb_e = GATED ? sb + ((size_t)e * nblk_out + blk_a) * nkb : sa_e;
 
@@ -264,6 +273,163 @@ __global__ __launch_bounds__(NTHREADS, 1) void ffn_gemm(const uint8_t* __restric
     // block kb+1 into registers.
     issue_x(0, 0);
     issue_w(0, 0);
+    if (narrow) {
+        // ---- NARROW tile: at most 64 rows.  In the layout above only the two waves of token group 0 would
+        //      multiply, alone on their SIMDs, and such a tile costs 0.7 of a full one.  Here all eight waves work:
+        //      wave w multiplies the 32 staged weight rows it copies itself by the tile's 64 token columns (two
+        //      32x32 products, four matrix instructions per K block), so the matrix work is spread over every SIMD
+        //      and the tile runs at the speed its weight tile streams in.  Same rings, same copy order, same
+        //      barrier per K block as the full tiles; nothing is overlapped by hand - the copies are the bound.
+        uint32_t offk[2][2];
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+                offk[ks][j] = (uint32_t)(((ks * 4 + half * 2 + j) ^ (l32 & 7) ^ ((l32 >> 3) & 1)) << 4);
+        const uint32_t a_row = (uint32_t)(wave * 32 + l32) * KB;
+        const uint32_t b_row = (uint32_t)(X_RING + l32 * KB);
+        uint32_t xs_i[2];
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) xs_i[ts] = 4u * (uint32_t)min(wk.row0 + ts * 32 + l32, n_rows - 1);
+        const size_t plane = (size_t)n_rows * 4;
+        auto xs_load = [&](float& dst, int kb, int ts) {
+            asm volatile("global_load_dword %0, %1, %2" : "=v"(dst) : "v"(xs_i[ts]),
+                         "s"(reinterpret_cast<const uint8_t*>(act_s) + (size_t)kb * plane) : "memory");
+        };
+        float xs_n[2], xs_cur[2];
+        xs_load(xs_n[0], 0, 0);
+        xs_load(xs_n[1], 0, 1);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts) asm volatile("v_mov_b32 %0, %1" : "=v"(xs_cur[ts]) : "v"(xs_n[ts]));
+        if (nkb > 1) {
+            xs_load(xs_n[0], 1, 0);
+            xs_load(xs_n[1], 1, 1);
+            issue_x(1, 1);
+            issue_w(1, 1);
+        }
+        if (nkb > 2) issue_w(2, 2);
+        v16f an[2];
+#pragma unroll
+        for (int ts = 0; ts < 2; ++ts)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) an[ts][r] = 0.f;
+        int wslot = 0;
+        for (int kb = 0; kb < nkb; ++kb) {
+            const uint8_t* sW = smem + wslot * W_TILE + a_row;
+            const uint8_t* sX = smem + b_row + (kb & 1) * X_TILE;
+            v8i a[2], b[2][2];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                a[ks] = lds_operand(sW, offk[ks][0], offk[ks][1]);
+                b[0][ks] = lds_operand(sX, offk[ks][0], offk[ks][1]);
+                b[1][ks] = lds_operand(sX + 32 * KB, offk[ks][0], offk[ks][1]);
+            }
+            const float wsa = sa_e[kb], wsb = sb_e[kb];
+            v16f T0, T1;
+            mfma_first(T0, a[0], b[0][0]);
+            mfma_acc(T0, a[1], b[0][1]);
+            mfma_first(T1, a[0], b[1][0]);
+            mfma_acc(T1, a[1], b[1][1]);
+            // this wave's reads of block kb are done (the operands are in registers): wait for the copies that must be
+            // complete (all but the weight block two steps ahead), meet the other waves, refill the freed slots
+            if (kb + 2 < nkb) asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+            const float x0 = xs_cur[0], x1 = xs_cur[1];
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts) asm volatile("v_mov_b32 %0, %1" : "=v"(xs_cur[ts]) : "v"(xs_n[ts]));
+            if (kb + 2 < nkb) {
+                xs_load(xs_n[0], kb + 2, 0);
+                xs_load(xs_n[1], kb + 2, 1);
+                issue_x(kb + 2, kb & 1);
+            }
+            if (kb + 3 < nkb) issue_w(kb + 3, wslot);
+            // the four matrix instructions have left the pipe by now; a few wait states more cost nothing here
+            asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");
+            PIN(T0);
+            PIN(T1);
+            // accumulator rows 0..15 of the product (registers 0..7) are gate rows, 16..31 (registers 8..15) up rows
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float w = (GATED && r >= 8) ? wsb : wsa;
+                an[0][r] = fmaf(x0 * w, T0[r], an[0][r]);
+                an[1][r] = fmaf(x1 * w, T1[r], an[1][r]);
+            }
+            PIN(an[0]);
+            PIN(an[1]);
+            wslot = (wslot == NW_BUF - 1) ? 0 : wslot + 1;
+        }
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();                          // every wave is done with the operand rings
+        asm volatile("" ::: "memory");
+        // ---- narrow epilogue.  Register r of an[ts] belongs to token row0 + ts*32 + l32 and staged row
+        //      32w + (r/4)*8 + half*4 + r%4 of this wave.
+        if (GATED) {
+            // registers 0..7: gate of features f0 + 16w + (r/4)*8 + half*4 + r%4, registers 8..15: up of the same
+            float h[2][8];
+            float amax[2] = {0.f, 0.f};
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts) {
+#pragma unroll
+                for (int r = 0; r < 8; ++r) {
+                    const float g = an[ts][r], u = an[ts][r + 8];
+                    const float v = g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+                    h[ts][r] = v;
+                    amax[ts] = fmaxf(amax[ts], fabsf(v));
+                }
+                amax[ts] = fmaxf(amax[ts], __shfl_xor(amax[ts], 32));
+                if (half == 0) s_amax[wave * 64 + ts * 32 + l32] = amax[ts];
+            }
+            __syncthreads();                                   // the 128 features of a token's group live in all 8 waves
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts) {
+                const int trow = ts * 32 + l32;
+                const int p = wk.row0 + trow;
+                float am = 0.f;
+#pragma unroll
+                for (int w = 0; w < 8; ++w) am = fmaxf(am, s_amax[w * 64 + trow]);
+                const float sc = (am == 0.f) ? 1.0f : am / 448.0f;
+                // the same correctly rounded quotient as in the full tiles' epilogue
+                float inv = __builtin_amdgcn_rcpf(sc);
+                inv = fmaf(fmaf(-sc, inv, 1.0f), inv, inv);
+                const bool mid_range = sc > 1e-30f && sc < 1e30f;
+                auto quot = [&](float hv) {
+                    const float q0 = hv * inv;
+                    return mid_range ? fmaf(fmaf(-q0, sc, hv), inv, q0) : hv / sc;
+                };
+                if (p < row_end) {
+                    uint8_t* dst = hq + (size_t)p * NOUT + f0 + wave * 16 + half * 4;
+#pragma unroll
+                    for (int r4 = 0; r4 < 2; ++r4) {
+                        int code = 0;
+                        code = __builtin_amdgcn_cvt_pk_fp8_f32(quot(h[ts][r4 * 4]), quot(h[ts][r4 * 4 + 1]), code, false);
+                        code = __builtin_amdgcn_cvt_pk_fp8_f32(quot(h[ts][r4 * 4 + 2]), quot(h[ts][r4 * 4 + 3]), code, true);
+                        *reinterpret_cast<uint32_t*>(dst + r4 * 8) = (uint32_t)code;
+                    }
+                    if (half == 0 && wave == 0) hs[(size_t)wk.ft * n_rows + p] = sc;
+                }
+            }
+        } else {
+            // 64 rows x 256 features: 16-byte pieces straight from the accumulator layout (a narrow tile's output is small)
+#pragma unroll
+            for (int ts = 0; ts < 2; ++ts) {
+                const int p = wk.row0 + ts * 32 + l32;
+                if (p >= row_end) continue;
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int fcol = f0 + wave * 32 + r4 * 8 + half * 4;
+                    if (fcol < NOUT)
+                        *reinterpret_cast<float4*>(y_perm + (size_t)p * NOUT + fcol) =
+                            make_float4(an[ts][r4 * 4], an[ts][r4 * 4 + 1], an[ts][r4 * 4 + 2], an[ts][r4 * 4 + 3]);
+                }
+            }
+        }
+        return;
+    }
     if (!wave_active) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
