@@ -190,9 +190,12 @@ int moe_expert_ffn_fp8_gather(moe_ctx* ctx, const uint8_t* xq_tok, const float* 
 /* Weighted combine back to token order:
  *   y[t,c] = bf16( sum_{j<k} topk_w[t,j] * y_perm[inv_perm[t*k+j], c] ),
  * fp32 fused multiply-adds in slot order, one rounding to bf16 at the end.
- *   y_perm [N,d] f32; inv_perm [N] i32; topk_w [T,k] f32; y_bf16 [T,d]. */
+ *   y_perm [N,d] f32; inv_perm [N] i32; topk_w [T,k] f32; y_bf16 [T,d].
+ *   y_f32 [T,d] f32 or NULL: if given, also receives the fp32 sums before the rounding (a parity aid: the
+ *   rounded outputs of two implementations differ by whole bf16 steps wherever their sums straddle a rounding
+ *   boundary, the sums themselves show the actual difference). */
 int moe_combine(moe_ctx* ctx, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
-                uint16_t* y_bf16);
+                uint16_t* y_bf16, float* y_f32);
 
 /* Length-based load balancing before rollout (paper section 3.1.1): distributes n samples over
  * n_groups worker groups so that the groups' total predicted generation lengths are about equal.

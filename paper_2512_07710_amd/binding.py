@@ -59,7 +59,7 @@ def load_library(path: Optional[str] = None) -> ctypes.CDLL:
     lib.moe_quantize_fp8.argtypes = [vp, vp, i64, i32, i32, vp, i32, vp, vp]
     lib.moe_expert_ffn_fp8.argtypes = [vp] * 11
     lib.moe_expert_ffn_fp8_gather.argtypes = [vp] * 12
-    lib.moe_combine.argtypes = [vp] * 5
+    lib.moe_combine.argtypes = [vp] * 6
     lib.moe_balance_lengths.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
     lib.moe_debug_copy_hidden.argtypes = [vp, vp, vp]
     lib.moe_probe_copy.argtypes = [vp, vp, vp, i64]
@@ -181,9 +181,10 @@ def moe_expert_ffn_fp8_gather(ctx, xq_tok, xs_tok, perm, offsets, W1, W3, W2, s1
                                                     _ptr(y_perm, f32)), "moe_expert_ffn_fp8_gather")
 
 
-def moe_combine(ctx, y_perm, inv_perm, topk_w, y) -> None:
+def moe_combine(ctx, y_perm, inv_perm, topk_w, y, y_f32=None) -> None:
     _check(load_library().moe_combine(ctx, _ptr(y_perm, torch.float32), _ptr(inv_perm, torch.int32),
-                                      _ptr(topk_w, torch.float32), _ptr(y, torch.bfloat16)), "moe_combine")
+                                      _ptr(topk_w, torch.float32), _ptr(y, torch.bfloat16),
+                                      _ptr(y_f32, torch.float32)), "moe_combine")
 
 
 def moe_balance_lengths(pred_len, n_groups: int, equal_count: bool = True):

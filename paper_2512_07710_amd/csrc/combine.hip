@@ -20,7 +20,7 @@ template <int KT>
 __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ y_perm,
                                                       const int32_t* __restrict__ inv_perm,
                                                       const float* __restrict__ topk_w, int T, int d, int k_rt,
-                                                      uint16_t* __restrict__ y) {
+                                                      uint16_t* __restrict__ y, float* __restrict__ y_f32) {
     __shared__ int32_t s_row[MAX_K];
     __shared__ float s_w[MAX_K];
     const int k = KT > 0 ? KT : k_rt;
@@ -72,6 +72,7 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
         o.x = f32_to_bf16_rne(acc.x) | (f32_to_bf16_rne(acc.y) << 16);
         o.y = f32_to_bf16_rne(acc.z) | (f32_to_bf16_rne(acc.w) << 16);
         *reinterpret_cast<uint2*>(y + (size_t)t * d + (size_t)c4 * 4) = o;
+        if (y_f32) *reinterpret_cast<float4*>(y_f32 + (size_t)t * d + (size_t)c4 * 4) = acc;   // the sums before rounding
     }
     (void)T;
 }
@@ -79,11 +80,11 @@ __global__ __launch_bounds__(256) void combine_kernel(const float* __restrict__ 
 }  // namespace
 
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
-                          uint16_t* y) {
+                          uint16_t* y, float* y_f32) {
     const moe_dims& D = c->dims;
 #define MOE_COMBINE(KT_)                                                                                  \
     hipLaunchKernelGGL(combine_kernel<KT_>, dim3(D.T), dim3(256), 0, c->stream, y_perm, inv_perm, topk_w, D.T, \
-                       D.d, D.k, y)
+                       D.d, D.k, y, y_f32)
     switch (D.k) {
         case 1: MOE_COMBINE(1); break;
         case 2: MOE_COMBINE(2); break;

@@ -206,11 +206,11 @@ int moe_expert_ffn_fp8_gather(moe_ctx* c, const uint8_t* xq_tok, const float* xs
 }
 
 int moe_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm, const float* topk_w,
-                uint16_t* y) {
+                uint16_t* y, float* y_f32) {
     if (!c) return MOE_EINVAL;
     if (c->dims.T == 0) return MOE_OK;
     if (!y_perm || !inv_perm || !topk_w || !y) return MOE_EINVAL;
-    return hip_rc(launch_combine(c, y_perm, inv_perm, topk_w, y));
+    return hip_rc(launch_combine(c, y_perm, inv_perm, topk_w, y, y_f32));
 }
 
 int moe_profile_enable(moe_ctx* c, int32_t on) {

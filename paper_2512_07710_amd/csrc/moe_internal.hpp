@@ -74,6 +74,6 @@ size_t ffn_work_bytes(int max_tiles, int F, int d);
 size_t route_workspace_bytes(int E, int d);
 size_t route_partial_bytes(int T, int E);
 hipError_t launch_combine(moe_ctx* c, const float* y_perm, const int32_t* inv_perm,
-                          const float* topk_w, uint16_t* y);
+                          const float* topk_w, uint16_t* y, float* y_f32);
 
 }  // namespace moe355

@@ -73,8 +73,9 @@ class MoELayer:
         B.moe_expert_ffn_fp8(self.ctx, self.xq, self.xs, self.offsets, w["W1q"], w["W3q"], w["W2q"], w["s1"],
                              w["s3"], w["s2"], self.y_perm)
 
-    def combine(self):
-        B.moe_combine(self.ctx, self.y_perm, self.inv_perm, self.topk_w, self.y)
+    def combine(self, y_f32=None):
+        """y_f32 [T,d] f32 (optional): also receives the sums before the bf16 rounding."""
+        B.moe_combine(self.ctx, self.y_perm, self.inv_perm, self.topk_w, self.y, y_f32)
 
     # ---- whole layer ----------------------------------------------------------------
     # `fused` = True: activations quantised once per token, gathered inside the gate/up GEMM;

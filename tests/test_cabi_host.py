@@ -66,7 +66,7 @@ def test_null_arguments_are_rejected(lib):
     assert lib.moe_linear_fp8(None, None, None, 4, 128, None, None, 128, None) == -1
     assert lib.moe_expert_ffn_fp8_gather(*([None] * 12)) == -1
     assert lib.moe_expert_ffn_fp8(*([None] * 11)) == -1
-    assert lib.moe_combine(*([None] * 5)) == -1
+    assert lib.moe_combine(*([None] * 6)) == -1
     assert lib.moe_debug_copy_hidden(None, None, None) == -1
     assert lib.moe_check_ids(None) == -1
     assert lib.moe_probe_copy(None, None, None, 1024) == -1

@@ -77,7 +77,7 @@ def test_empty_batch(gpu_lib):
         gpu_lib.moe_expert_ffn_fp8(ctx, xq, xs, offsets, W, W, W2, s13, s13, s2, y_perm)
         gpu_lib.moe_expert_ffn_fp8_gather(ctx, xq, xs, perm, offsets, W, W, W2, s13, s13, s2, y_perm)
         y = torch.empty((0, d), dtype=torch.bfloat16, device=dev)
-        gpu_lib.moe_combine(ctx, y_perm, inv, w, y)
+        gpu_lib.moe_combine(ctx, y_perm, inv, w, y, None)
         torch.cuda.synchronize()
     finally:
         gpu_lib.moe_destroy(ctx)

@@ -224,9 +224,16 @@ def _whole_tensor_gate(gpu_lib, ci):
     rel = _rel_l2(y_g, ref)
     per_tok = np.sqrt(np.sum((y_g - ref) ** 2, axis=1) / np.maximum(np.sum(ref ** 2, axis=1), 1e-300))
     flips = _combine_alone(r, r.y)
-    print(f"[{cfg.name}/{r.mode}] WHOLE TENSOR: layer rel-L2 {rel:.3e}, y_perm rel-L2 {rel_perm:.3e} (bar {REL_L2_BAR}); "
-          f"per-token max {per_tok.max():.3e}; combine alone: {flips:.2e} bf16 roundings differ")
+    # the GPU's sums before the output rounding against the oracle's unrounded output
+    y_f32 = torch.empty((cfg.T, cfg.d), dtype=torch.float32, device=DEV)
+    r.layer.combine(y_f32)
+    torch.cuda.synchronize()
+    assert torch.equal(r.layer.y.view(torch.int16), r.y.view(torch.int16))
+    pre = _rel_l2(y_f32.cpu().numpy(), y_o)
+    print(f"[{cfg.name}/{r.mode}] WHOLE TENSOR: layer rel-L2 {rel:.3e}, before the output rounding {pre:.3e}, y_perm rel-L2 "
+          f"{rel_perm:.3e} (bar {REL_L2_BAR}); per-token max {per_tok.max():.3e}; combine alone: {flips:.2e} bf16 roundings differ")
     assert rel_perm <= REL_L2_BAR
+    assert pre <= REL_L2_BAR
     assert rel <= REL_L2_BAR
     _fused_is_bit_identical(r)
 
@@ -339,20 +346,18 @@ def _sample_error(r, y_gpu, w, label, ref_rows=None):
     est = float(np.sqrt(num_t.sum() / den))
     se = float(0.5 * np.sqrt(CFG4_TOKENS * np.var(num_t)) / den / max(est, 1e-30))   # tokens are the sampling unit
     halves = [float(np.sqrt(num_t[h::2].sum() / np.sum(ref[h::2] ** 2))) for h in (0, 1)]
-    # the GPU's own expert rows combined in fp64: the layer's error before the output rounding
-    rows = r.inv_perm.reshape(cfg.T, cfg.k)[:CFG4_TOKENS] if label == "routed" else None
     unrounded = _rel_l2(got, y_ref)                       # GPU bf16 against the oracle's unrounded output
     fmt = _rel_l2(ref, y_ref)                             # what rounding the exact output to bf16 costs by itself
+    # the GPU's own fp32 sums before the output rounding (moe_combine's second output) against the same
+    y_f32 = torch.empty((cfg.T, cfg.d), dtype=torch.float32, device=DEV)
+    r.layer.combine(y_f32)
+    torch.cuda.synchronize()
+    pre = _rel_l2(y_f32[:CFG4_TOKENS].cpu().numpy(), y_ref)
     print(f"[{cfg.name}/{label}] layer rel-L2 over tokens 0..{CFG4_TOKENS - 1}: {est:.3e} +- {se:.1e} (bar {REL_L2_BAR}); "
           f"even / odd tokens {halves[0]:.3e} / {halves[1]:.3e}; per-token max "
-          f"{np.sqrt(num_t / np.sum(ref ** 2, axis=1)).max():.3e}; against the unrounded oracle output {unrounded:.3e}, "
-          f"of which the bf16 format alone {fmt:.3e}")
-    if rows is not None:
-        yp = r.layer.y_perm[_dev(rows.reshape(-1))].cpu().numpy().astype(np.float64).reshape(CFG4_TOKENS, cfg.k, cfg.d)
-        y_g64 = np.einsum("tk,tkd->td", w[:CFG4_TOKENS].astype(np.float64), yp)
-        pre = _rel_l2(y_g64, y_ref)
-        print(f"[{cfg.name}/{label}] before the output rounding (GPU expert rows combined in fp64): {pre:.3e}")
-        assert pre <= REL_L2_BAR
+          f"{np.sqrt(num_t / np.sum(ref ** 2, axis=1)).max():.3e}; before the output rounding {pre:.3e}; bf16 output "
+          f"against the unrounded oracle output {unrounded:.3e}, of which the bf16 format alone {fmt:.3e}")
+    assert pre <= REL_L2_BAR
     # hard gates: what the GPU's output is off the exact output beyond the bf16 format's own rounding stays
     # under the bar, and the bf16-against-bf16 figure stays within a tenth of the bar
     assert np.sqrt(max(unrounded ** 2 - fmt ** 2, 0.0)) <= REL_L2_BAR
