@@ -22,6 +22,13 @@ class MoELayer:
         with torch.cuda.device(self.device):
             self.stream = stream if stream is not None else torch.cuda.current_stream()
             self.ctx = B.moe_create(T, d, E, k, F, self.stream)
+            # a second stream (default priority) and an empty-batch context bound to it: the per-token quantisation does
+            # not depend on the routing decision, so the whole-layer calls below run it beside the routing kernels
+            self.side_stream = torch.cuda.Stream(device=self.device)
+            self.side_ctx = B.moe_create(0, d, E, k, F, self.side_stream)
+        # worth it only for large batches (measured: 0.2 ms off the 13.8 ms step at T = 32768, d = 7168; at T = 4096 and
+        # below the two stream hand-overs cost more than the 0.03 ms the quantisation takes)
+        self.overlap_quantize = T * d >= (1 << 26)
         dev, N = self.device, max(self.N, 1)
         self.topk_idx = torch.empty((T, k), dtype=torch.int32, device=dev)
         self.topk_w = torch.empty((T, k), dtype=torch.float32, device=dev)
@@ -36,6 +43,9 @@ class MoELayer:
         self.y = torch.empty((T, d), dtype=torch.bfloat16, device=dev)
 
     def close(self):
+        if getattr(self, "side_ctx", None):
+            B.moe_destroy(self.side_ctx)
+            self.side_ctx = None
         if getattr(self, "ctx", None):
             B.moe_destroy(self.ctx)
             self.ctx = None
@@ -90,11 +100,30 @@ class MoELayer:
         self.combine()
         return self.y
 
+    def _quantize_tokens_beside(self, x):
+        """Token-order quantisation on the side stream; the caller's stream waits for it before the expert FFN."""
+        self.side_stream.wait_stream(self.stream)           # x, and the previous step's readers of xq_tok / xs_tok
+        B.moe_quantize_fp8(self.side_ctx, x, self.T, self.d, 128, None, 1, self.xq_tok, self.xs_tok)
+
+    def _ffn_after_side(self, w):
+        self.stream.wait_stream(self.side_stream)
+        self.expert_ffn_gather(w)
+        self.combine()
+        return self.y
+
     def forward_routed(self, x, W_r, sel_bias, w, fused=True):
+        if fused is True and self.overlap_quantize:
+            self._quantize_tokens_beside(x)
+            self.route(x, W_r, sel_bias)
+            return self._ffn_after_side(w)
         self.route(x, W_r, sel_bias)
         return self._ffn(x, w, fused)
 
     def forward_replay(self, x, logged_idx, logged_w, w, fused=True):
+        if fused is True and self.overlap_quantize:
+            self._quantize_tokens_beside(x)
+            self.route_replay(x, logged_idx, logged_w)
+            return self._ffn_after_side(w)
         self.route_replay(x, logged_idx, logged_w)
         return self._ffn(x, w, fused)
 
