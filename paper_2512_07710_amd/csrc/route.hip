@@ -25,6 +25,10 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int NO_CAND = 0x7FFFFFFF;
+// Batches of at most ROUTE_SPLIT_MAX_T tokens (fewer 32-token tiles than half the compute units) run the K loop
+// split over up to ROUTE_MAX_SPLITS blocks per token tile: as many as bring the grid to about 256 blocks.
+constexpr int ROUTE_SPLIT_MAX_T = 4096;
+constexpr int ROUTE_MAX_SPLITS = 16;
 
 __device__ inline uint32_t f32_to_bf16_rne_bits(float v) {
     const uint32_t b = __float_as_uint(v);
@@ -465,9 +469,15 @@ __global__ __launch_bounds__(256) void route_finish_kernel(const float* __restri
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int e = lane + 64 * i;
+        // all partials are requested before the first is added (a loop of load-then-add would pay one memory round trip
+        // per split); they are added in split order, absent splits as zeros
+        float part[ROUTE_MAX_SPLITS];
+#pragma unroll
+        for (int sp = 0; sp < ROUTE_MAX_SPLITS; ++sp)
+            part[sp] = (e < E_pad && sp < splits) ? partial[((size_t)sp * T_pad + t) * E_pad + e] : 0.f;
         float v = 0.f;
-        if (e < E_pad)
-            for (int sp = 0; sp < splits; ++sp) v += partial[((size_t)sp * T_pad + t) * E_pad + e];
+#pragma unroll
+        for (int sp = 0; sp < ROUTE_MAX_SPLITS; ++sp) v += part[sp];
         lg[i] = v;
         sc[i] = e < E ? v + (bias ? bias[e] : 0.f) : -INFINITY;
     }
@@ -515,10 +525,6 @@ size_t route_workspace_bytes(int E, int d) {
     return (size_t)3 * E_pad * d * sizeof(uint16_t);
 }
 
-// Batches of at most ROUTE_SPLIT_MAX_T tokens (fewer 32-token tiles than half the compute units) run the K loop
-// split over up to ROUTE_MAX_SPLITS blocks per token tile: as many as bring the grid to about 256 blocks.
-constexpr int ROUTE_SPLIT_MAX_T = 4096;
-constexpr int ROUTE_MAX_SPLITS = 16;
 
 static int route_splits_for(int T) {
     const int tiles = (T + 31) / 32;
