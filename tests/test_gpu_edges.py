@@ -105,3 +105,26 @@ def test_route_token_tile_variants(gpu_lib, T, d, E, k):
         assert torch.equal(layer.topk_idx, idx) and torch.equal(layer.topk_w.view(torch.int32), w.view(torch.int32))
     finally:
         layer.close()
+
+
+def _random_shape(i):
+    """A seeded random shape with at least 2^17 hidden activations: the 2e-3 bar is a statement about large tensors
+    (one e4m3 step the other way in the hidden activations moves a row of a d = F = 128 layer by half a percent, and a
+    few dozen of them are expected whatever the size), so shapes too small for the law of large numbers are drawn again."""
+    rng = np.random.default_rng(2024 + i)
+    while True:
+        E = int(rng.choice([1, 2, 3, 5, 8, 17, 40, 64, 130, 256]))
+        k = int(min(E, rng.choice([1, 2, 3, 6, 8, 16])))
+        T = int(rng.choice([1, 7, 33, 64, 65, 129, 300, 700, 1500, 2500]))
+        d, F = 128 * int(rng.integers(1, 7)), 128 * int(rng.integers(1, 5))
+        if T * k * F >= 1 << 17:
+            return MoEConfig(f"rand{i}", T=T, d=d, E=E, k=k, F=F, modes=("routed", "replay"), seed=100 + i)
+
+
+@pytest.mark.parametrize("i", range(10))
+def test_random_small_shapes(gpu_lib, i):
+    """Seeded random shapes (1 to 2500 tokens, 1 to 256 experts, any fan-out, one to six K blocks) through the whole
+    layer against the oracle, stage by stage: between them they take the split and the single-pass router, the
+    single-block and the chunked permutation, narrow, ragged and full GEMM tiles."""
+    cfg = _random_shape(i)
+    _run_and_check_layer(gpu_lib, cfg, "routed" if i % 3 else "replay")
