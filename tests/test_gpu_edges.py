@@ -128,3 +128,55 @@ def test_random_small_shapes(gpu_lib, i):
     single-block and the chunked permutation, narrow, ragged and full GEMM tiles."""
     cfg = _random_shape(i)
     _run_and_check_layer(gpu_lib, cfg, "routed" if i % 3 else "replay")
+
+
+@pytest.mark.parametrize("mode", ["routed", "replay"])
+def test_layer_under_hip_graph_capture(gpu_lib, mode):
+    """The whole layer recorded into a HIP graph (decode-sized batch, where launches are a visible share of the step) and
+    replayed several times with eager work and synchronisations in between: every replay must reproduce the eager result
+    bit for bit, also after the inputs have changed in place.  The library enqueues kernels only (no memsets, no
+    allocations, no synchronisation) in these calls, which is what makes them capturable."""
+    from workloads import make_inputs
+    cfg = MoEConfig("graph", T=192, d=512, E=16, k=4, F=384, modes=("routed", "replay"), seed=77)
+    inp = make_inputs(cfg)
+    dv = {n: (v.cuda() if isinstance(v, torch.Tensor) else v) for n, v in inp.items()}
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        layer = gpu_lib.MoELayer(cfg.T, cfg.d, cfg.E, cfg.k, cfg.F, stream=stream)
+        try:
+            x = dv["x"].clone()
+            layer.forward_routed(x, dv["W_r"], None, dv)              # eager warm-up: one-time attribute calls happen here
+            stream.synchronize()
+            log_idx, log_w = layer.topk_idx.clone(), layer.topk_w.clone()
+
+            def step():
+                if mode == "routed":
+                    layer.forward_routed(x, dv["W_r"], None, dv)
+                else:
+                    layer.forward_replay(x, log_idx, log_w, dv)
+
+            step()
+            stream.synchronize()
+            want = layer.y.clone()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=stream):
+                step()
+            for rep in range(3):
+                layer.y.zero_()
+                layer.y_perm.zero_()
+                graph.replay()
+                stream.synchronize()
+                assert torch.equal(layer.y.view(torch.int16), want.view(torch.int16)), f"replay {rep}"
+                _ = (dv["W_r"] * 2).sum().item()                     # the program's own eager work between replays
+            # other activations in the same buffers: the graph reads them, and the eager path agrees
+            x.copy_(torch.roll(dv["x"], 5, dims=0))
+            graph.replay()
+            stream.synchronize()
+            got = layer.y.clone()
+            step()
+            stream.synchronize()
+            assert torch.equal(got.view(torch.int16), layer.y.view(torch.int16))
+            if mode == "routed":
+                assert not torch.equal(got.view(torch.int16), want.view(torch.int16))
+        finally:
+            layer.close()
