@@ -13,6 +13,11 @@
 // token with register scans and one cross-half shuffle per round (larger score wins,
 // equal scores go to the lower expert index), and a final pass merges the four waves'
 // candidates, applies the softmax over the k selected unbiased logits and writes out.
+//
+// Batches of at most 4096 tokens would give that kernel fewer blocks than half the compute units.
+// They take 32-token tiles whose K loop is split over up to 16 blocks; each block writes its
+// partial logits, and a second kernel (one wave per token) adds them up in split order and does
+// the same selection with wave-wide reductions.
 #include "moe_internal.hpp"
 
 #include <type_traits>
