@@ -85,3 +85,20 @@ def test_noalloc_replay_validates_before_touching_a_device(lib):
 def test_binding_fails_loudly_without_library(tmp_path):
     with pytest.raises(moe.MoEError):
         moe.load_library(str(tmp_path / "missing.so"))
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 with nothing but <stdint.h>, and every entry point it
+    declares must be usable from C (a translation unit that takes each one's address)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no gcc")
+    header = open(os.path.join(ROOT, "include", "moe355.h")).read()
+    names = sorted(set(re.findall(r"\b(moe_[a-z0-9_]+)\s*\(", re.sub(r"/\*.*?\*/", "", header, flags=re.S))))
+    src = tmp_path / "use.c"
+    src.write_text('#include "moe355.h"\ntypedef void (*fn)(void);\nfn table[] = {' + ", ".join(f"(fn){n}" for n in names) + "};\n")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
